@@ -1,0 +1,4 @@
+"""CPU oracle (test infrastructure only; see arrol_oracle.py)."""
+from .arrol_oracle import (bf16_bits_to_f64, score, quantise, select_group, select,
+                           compact, log_softmax_rows, logprob, weighted_vote,
+                           FIXED_POINT_BITS)

@@ -1,0 +1,248 @@
+"""CPU oracle for the ARRoL online rollout-pruning data path.
+
+THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is a plain, slow, obviously
+correct restatement of what each stage computes, written from the paper
+("Prune as You Generate: Online Rollout Pruning for Faster and Better RLVR").
+Floating point is float64 on the exact values of the bf16 / fp32 inputs;
+integer stages use unbounded Python integers.  It shares no code with the HIP
+library and must never be imported by it.  Only the test-suite, the smoke
+check and the benchmark's cpu_baseline leg may call it.
+
+Every function is pinned by CPU tests to facts the paper and the mathematics
+fix (closed forms, invariants, brute force in exact rationals); none is
+"parity unpinned".
+
+Stages (paper passages in each docstring):
+  score          quality head + sigmoid            Sec. 4.2, App. A.4
+  select         balance rule iterated G-K times   Sec. 4.1 Thm 4.2, App. A.1
+  compact        survivor gather / re-batch        Sec. 4.3 (i),(ii); Alg. 1
+  logprob        log pi(o_t | o_<t)                Sec. 3 (GRPO ratio); Alg. 1
+  weighted_vote  rank-weighted answer vote         Sec. 4.4
+"""
+import math
+
+import numpy as np
+
+FIXED_POINT_BITS = 30  # probabilities are read on a 2**-30 grid by select()
+
+
+# ----------------------------------------------------------------------------
+# helpers: exact widening of bf16 bit patterns
+# ----------------------------------------------------------------------------
+def bf16_bits_to_f64(bits):
+    """uint16 bf16 bit patterns -> float64, exactly (bf16 is the top half of
+    an IEEE binary32)."""
+    bits = np.ascontiguousarray(bits, dtype=np.uint16)
+    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+# ----------------------------------------------------------------------------
+# stage 1: score
+# ----------------------------------------------------------------------------
+def score(hidden_bits, w, bias=0.0):
+    """Quality-head score and its sigmoid.
+
+    Sec. 4.2 ("Quality Score Prediction"): a small head on the backbone's
+    hidden state gives a scalar s_i per partial rollout.  App. A.4: the score
+    is squashed into [0,1] with the sigmoid.  Reading used here: the head is
+    one linear layer, s_i = <w, h_i> + b, and the squashed score is the
+    success probability q_i handed to the selection stage.
+
+    hidden_bits : [N, d] uint16 (bf16 bit patterns)
+    w           : [d] float32, bias: float
+    returns (s, q) float64 [N]
+    """
+    h = bf16_bits_to_f64(hidden_bits)
+    w64 = np.asarray(w, dtype=np.float32).astype(np.float64)
+    n = h.shape[0]
+    s = np.empty(n, dtype=np.float64)
+    for i in range(n):
+        s[i] = math.fsum(h[i] * w64) + float(bias)
+    q = np.empty(n, dtype=np.float64)
+    for i in range(n):
+        if s[i] >= 0.0:
+            q[i] = 1.0 / (1.0 + math.exp(-s[i]))
+        else:  # same function, written so exp never overflows
+            e = math.exp(s[i])
+            q[i] = e / (1.0 + e)
+    return s, q
+
+
+# ----------------------------------------------------------------------------
+# stage 2: select
+# ----------------------------------------------------------------------------
+def quantise(prob_f32):
+    """fp32 probabilities -> integers on the 2**-30 grid, rounding the fp32
+    product to nearest-even *in fp32* (the product by a power of two is exact,
+    so this is a pure rounding of the given value).  Both the oracle and the
+    library take the selection decision on these integers."""
+    p = np.asarray(prob_f32, dtype=np.float32)
+    scaled = p * np.float32(2.0 ** FIXED_POINT_BITS)      # exact in fp32
+    return [int(v) for v in np.rint(scaled).astype(np.int64)]
+
+
+def select_group(k, K, R):
+    """One prompt group.  k: list of G fixed-point probabilities, R: fixed-point
+    target ratio rho.  Sec. 4.1, Thm 4.2 / App. A.1: with live set A,
+        mu_{-j} = (1/(|A|-1)) * sum_{i in A, i != j} q_i
+        j_hat   = argmin_{j in A} | mu_{-j} - rho |
+    and j_hat is pruned.  The rule is applied again to the shrunken group until
+    K rollouts remain.  Ties in the argmin go to the lowest index.
+
+    |mu_{-j} - rho| is compared over a common denominator (|A|-1) * 2**30, so
+    everything below is exact integer arithmetic on the definition itself.
+    Returns (survivors ascending, removal order)."""
+    live = list(range(len(k)))
+    removed = []
+    while len(live) > K:
+        n = len(live)
+        best_j, best_dev = None, None
+        for j in live:
+            rest = sum(k[i] for i in live if i != j)       # (n-1) * mu_{-j} * 2^30
+            dev = abs(rest - R * (n - 1))                  # (n-1) * |mu_{-j}-rho| * 2^30
+            if best_dev is None or dev < best_dev:
+                best_j, best_dev = j, dev
+        live.remove(best_j)
+        removed.append(best_j)
+    return live, removed
+
+
+def select(prob_f32, n_groups, G, K, rho=0.5):
+    """Exactly-K, correctness-balanced survivors for every prompt group.
+
+    prob_f32: [n_groups*G] float32, groups are consecutive runs of G rollouts.
+    Returns keep_mask uint8 [n_groups*G] and survivor_idx int32 [n_groups*K]
+    (global rollout ids, ascending within a group, groups in order)."""
+    if not (1 <= K <= G):
+        raise ValueError("need 1 <= K <= G")
+    k_all = quantise(prob_f32)
+    if len(k_all) != n_groups * G:
+        raise ValueError("prob has wrong length")
+    R = quantise(np.array([rho], dtype=np.float32))[0]
+    keep = np.zeros(n_groups * G, dtype=np.uint8)
+    surv = np.empty(n_groups * K, dtype=np.int32)
+    for g in range(n_groups):
+        live, _ = select_group(k_all[g * G:(g + 1) * G], K, R)
+        for r, j in enumerate(live):
+            keep[g * G + j] = 1
+            surv[g * K + r] = g * G + j
+    return keep, surv
+
+
+# ----------------------------------------------------------------------------
+# stage 3: compact
+# ----------------------------------------------------------------------------
+def compact(kv_src, block_table_src, seq_len_src, tokens_src, survivor_idx,
+            n_pages_dst, fill=0):
+    """Gather the survivors' paged KV cache and token buffers into a dense pool.
+
+    Sec. 4.3 (i): pruned requests leave the pool at once so their capacity is
+    reused; (ii) / Alg. 1 "Filter pruned rollouts, rebatch": survivors are
+    re-batched.  The paper fixes no layout; this build's contract is:
+
+    kv_src          [L, 2, P_src, page_tokens, H_kv, hd] uint16 (bf16 bits)
+    block_table_src [N, ppr] int32, seq_len_src [N] int32, tokens_src [N, max_len] int32
+    survivor_idx    [N_k] int32, ascending rollout ids
+    Survivor rank r owns np_r = ceil(seq_len/page_tokens) destination pages
+    starting at base_r = sum_{r'<r} np_r'; whole pages are copied verbatim.
+
+    Returns dict(kv_dst, block_table_dst, seq_len_dst, tokens_dst, src_of_dst,
+    n_pages_used).  Untouched destination pages hold `fill`."""
+    L, two, _, page_tokens, H, hd = kv_src.shape
+    assert two == 2
+    n_keep = len(survivor_idx)
+    ppr = block_table_src.shape[1]
+    kv_dst = np.full((L, 2, n_pages_dst, page_tokens, H, hd), fill, dtype=kv_src.dtype)
+    bt_dst = np.full((n_keep, ppr), -1, dtype=np.int32)
+    sl_dst = np.empty(n_keep, dtype=np.int32)
+    tok_dst = np.empty((n_keep, tokens_src.shape[1]), dtype=np.int32)
+    src_of_dst = np.empty(n_keep, dtype=np.int32)
+    base = 0
+    for r in range(n_keep):
+        src = int(survivor_idx[r])
+        n_pages = -(-int(seq_len_src[src]) // page_tokens)
+        for p in range(n_pages):
+            sp = int(block_table_src[src, p])
+            for layer in range(L):
+                for c in range(2):
+                    kv_dst[layer, c, base + p] = kv_src[layer, c, sp]
+            bt_dst[r, p] = base + p
+        sl_dst[r] = seq_len_src[src]
+        tok_dst[r, :] = tokens_src[src, :]
+        src_of_dst[r] = src
+        base += n_pages
+    return dict(kv_dst=kv_dst, block_table_dst=bt_dst, seq_len_dst=sl_dst,
+                tokens_dst=tok_dst, src_of_dst=src_of_dst, n_pages_used=base)
+
+
+# ----------------------------------------------------------------------------
+# stage 4: logprob
+# ----------------------------------------------------------------------------
+def log_softmax_rows(hidden_bits, lm_head_bits):
+    """Full float64 log-softmax over the vocabulary for every row:
+    z = W h, log_softmax(z)_v = z_v - (m + log sum_v exp(z_v - m)), m = max z."""
+    h = bf16_bits_to_f64(hidden_bits)
+    W = bf16_bits_to_f64(lm_head_bits)
+    z = h @ W.T
+    m = z.max(axis=1, keepdims=True)
+    lse = m + np.log(np.exp(z - m).sum(axis=1, keepdims=True))
+    return z - lse, lse[:, 0]
+
+
+def logprob(hidden_bits, lm_head_bits, targets):
+    """Per-token log-probability of the sampled token under the policy,
+    log pi_theta(o_t | o_<t): the quantity inside GRPO's importance ratio
+    (Sec. 3) that the frontend computes on the re-batched survivors (Sec. 4.3
+    (ii); Alg. 1 "Compute rewards, log-probs").  Temperature 1, no LM-head
+    bias; row t of `hidden` is already aligned with targets[t].
+
+    hidden_bits [T, d] uint16, lm_head_bits [V, d] uint16, targets [T] int.
+    Returns (logp, lse) float64 [T].  Rows are processed in small batches only
+    to bound memory; each row's arithmetic is the definition above."""
+    T = hidden_bits.shape[0]
+    targets = np.asarray(targets, dtype=np.int64)
+    W = bf16_bits_to_f64(lm_head_bits)
+    logp = np.empty(T, dtype=np.float64)
+    lse = np.empty(T, dtype=np.float64)
+    step = max(1, min(T, (1 << 25) // max(1, W.shape[0])))
+    for t0 in range(0, T, step):
+        h = bf16_bits_to_f64(hidden_bits[t0:t0 + step])
+        z = h @ W.T
+        m = z.max(axis=1)
+        l = m + np.log(np.exp(z - m[:, None]).sum(axis=1))
+        lse[t0:t0 + step] = l
+        logp[t0:t0 + step] = z[np.arange(z.shape[0]), targets[t0:t0 + step]] - l
+    return logp, lse
+
+
+# ----------------------------------------------------------------------------
+# stage 5: weighted vote
+# ----------------------------------------------------------------------------
+def weighted_vote(prob_f32, answer_id, n_questions, C, A):
+    """Rank-weighted vote (Sec. 4.4): candidates are sorted by head score and
+    their ranks rescaled linearly to [0,1]; the answer with the largest summed
+    weight wins.  Readings: higher score = higher rank; equal scores share the
+    average of their ranks; ranks are kept as integers by doubling
+    (rank2_i = 2*#{q_j < q_i} + #{j != i: q_j == q_i}, weight = rank2/(2(C-1)));
+    the argmax runs over answer ids that occur among the candidates, lowest id
+    on equal tallies.
+
+    Returns winner int32 [Q], tally int64 [Q, A] in rank2 units."""
+    q = np.asarray(prob_f32, dtype=np.float32).reshape(n_questions, C)
+    ans = np.asarray(answer_id, dtype=np.int64).reshape(n_questions, C)
+    winner = np.empty(n_questions, dtype=np.int32)
+    tally = np.zeros((n_questions, A), dtype=np.int64)
+    for u in range(n_questions):
+        rank2 = []
+        for i in range(C):
+            below = sum(1 for j in range(C) if q[u, j] < q[u, i])
+            equal = sum(1 for j in range(C) if j != i and q[u, j] == q[u, i])
+            rank2.append(2 * below + equal)
+        for i in range(C):
+            tally[u, ans[u, i]] += rank2[i]
+        best = None
+        for a in sorted(set(int(x) for x in ans[u])):
+            if best is None or tally[u, a] > tally[u, best]:
+                best = a
+        winner[u] = best
+    return winner, tally

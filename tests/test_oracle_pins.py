@@ -1,0 +1,426 @@
+"""Pins for the CPU oracle: every oracle function is checked against something
+other than itself -- closed forms, invariants, exact-rational brute force of the
+paper's definitions, and hand-derived examples.  The paper prints no worked
+numeric example for any stage, so there are no paper-printed goldens."""
+import itertools
+import math
+import random
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle as O
+
+
+def f32_to_bf16_bits(x):
+    """Round-to-nearest-even float32 -> bf16 bit patterns (test-side helper)."""
+    u = np.asarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    r = (u + 0x7FFF + ((u >> 16) & 1)) >> 16
+    return r.astype(np.uint16)
+
+
+def bits_to_fraction(b):
+    """Exact rational value of one bf16 bit pattern (finite)."""
+    b = int(b)
+    sign = -1 if b >> 15 else 1
+    e = (b >> 7) & 0xFF
+    m = b & 0x7F
+    if e == 0:
+        return sign * Fraction(m, 1 << 7) * Fraction(1, 1 << 126)
+    return sign * (1 + Fraction(m, 1 << 7)) * (Fraction(2) ** (e - 127))
+
+
+# ----------------------------------------------------------------------------- bf16
+def test_bf16_widening_is_exact():
+    vals = np.array([0.0, 1.0, -2.0, 0.5, 1.5, 3.140625, -0.0078125], dtype=np.float32)
+    bits = f32_to_bf16_bits(vals)
+    out = O.bf16_bits_to_f64(bits)
+    assert np.array_equal(out, vals.astype(np.float64))
+    for b, v in zip(bits, out):
+        assert bits_to_fraction(b) == Fraction(float(v))
+
+
+# ----------------------------------------------------------------------------- score
+def test_score_zero_weight_gives_half():
+    rng = np.random.default_rng(1)
+    h = f32_to_bf16_bits(rng.standard_normal((5, 16)))
+    s, q = O.score(h, np.zeros(16, np.float32), 0.0)
+    assert np.all(s == 0.0) and np.all(q == 0.5)
+
+
+def test_score_one_hot_picks_weight():
+    d = 24
+    rng = np.random.default_rng(2)
+    w = rng.standard_normal(d).astype(np.float32)
+    for k, c in [(0, 1.5), (7, -2.0), (23, 0.25)]:
+        h = np.zeros((1, d), np.float32)
+        h[0, k] = c
+        s, q = O.score(f32_to_bf16_bits(h), w, 0.0)
+        assert s[0] == c * float(w[k])
+        assert abs(q[0] - 0.5 * (1.0 + math.tanh(0.5 * s[0]))) < 1e-15
+
+
+def test_score_exact_rational_dot_and_bias():
+    rng = np.random.default_rng(3)
+    N, d = 4, 32
+    hb = f32_to_bf16_bits(rng.standard_normal((N, d)))
+    w = rng.standard_normal(d).astype(np.float32)
+    bias = 0.375
+    s, q = O.score(hb, w, bias)
+    for i in range(N):
+        exact = sum(bits_to_fraction(hb[i, k]) * Fraction(float(w[k])) for k in range(d)) + Fraction(bias)
+        assert abs(s[i] - float(exact)) <= 1e-14 * max(1.0, abs(float(exact)))
+        # sigmoid through the tanh identity, an independent closed form
+        assert abs(q[i] - 0.5 * (1.0 + math.tanh(0.5 * float(exact)))) < 1e-14
+
+
+def test_score_symmetry_monotone_saturation():
+    rng = np.random.default_rng(4)
+    h = rng.standard_normal((16, 8)).astype(np.float32)
+    hb = f32_to_bf16_bits(h)
+    hb_neg = hb ^ np.uint16(0x8000)            # exact negation of every element
+    w = rng.standard_normal(8).astype(np.float32)
+    s, q = O.score(hb, w)
+    s2, q2 = O.score(hb_neg, w)
+    assert np.allclose(s2, -s, rtol=0, atol=0)
+    assert np.allclose(q + q2, 1.0, rtol=0, atol=1e-15)
+    order = np.argsort(s)
+    assert np.all(np.diff(q[order]) >= 0)
+    for b, lo, hi in [(100.0, 1.0 - 1e-40, 1.0), (-100.0, 0.0, 1e-40)]:
+        _, qq = O.score(hb[:1], np.zeros(8, np.float32), b)
+        assert np.isfinite(qq[0]) and lo <= qq[0] <= hi
+    _, qq = O.score(hb[:1], np.zeros(8, np.float32), -1000.0)
+    assert qq[0] == 0.0
+
+
+# ----------------------------------------------------------------------------- select
+def definition_in_rationals(q_frac, K, rho):
+    """The paper's rule evaluated literally in exact rationals (Thm 4.2):
+    mu_{-j} = mean of the live probabilities without j; prune argmin |mu_{-j}-rho|,
+    first index on ties; repeat until K remain."""
+    live = list(range(len(q_frac)))
+    order = []
+    while len(live) > K:
+        devs = []
+        for j in live:
+            others = [q_frac[i] for i in live if i != j]
+            mu = sum(others) / len(others)
+            devs.append(abs(mu - rho))
+        j_hat = live[devs.index(min(devs))]
+        live.remove(j_hat)
+        order.append(j_hat)
+    return live, order
+
+
+def test_select_matches_rational_definition_random():
+    rnd = random.Random(7)
+    for trial in range(300):
+        G = rnd.randint(2, 9)
+        K = rnd.randint(1, G)
+        if trial % 3 == 0:   # coarse grid: many exact ties
+            q = np.array([rnd.randint(0, 16) / 16.0 for _ in range(G)], dtype=np.float32)
+        else:
+            q = np.array([rnd.random() for _ in range(G)], dtype=np.float32)
+        rho32 = np.float32(rnd.choice([0.5, 0.25, 0.7, 0.0, 1.0]))
+        k = O.quantise(q)
+        R = O.quantise(np.array([rho32]))[0]
+        q_frac = [Fraction(v, 1 << 30) for v in k]
+        live_def, order_def = definition_in_rationals(q_frac, K, Fraction(R, 1 << 30))
+        live, order = O.select_group(k, K, R)
+        assert live == live_def and order == order_def
+
+
+def test_select_closed_form_closest_to_t():
+    # |mu_{-j} - rho| = |S - q_j - rho (n-1)| / (n-1): the pruned rollout is the
+    # live one closest to t = S - rho (n-1)
+    rnd = random.Random(11)
+    for _ in range(200):
+        G = rnd.randint(2, 16)
+        k = [rnd.randint(0, 1 << 30) for _ in range(G)]
+        R = rnd.randint(0, 1 << 30)
+        live, order = O.select_group(k, G - 1, R)
+        t = sum(k) - R * (G - 1)
+        dist = [abs(v - t) for v in k]
+        assert order[0] == dist.index(min(dist))
+
+
+def test_select_quantise_is_round_half_even_on_fp32():
+    q = np.array([0.5, 0.25, 1.0, 0.0, 2.0 ** -31, 3 * 2.0 ** -31, 1 - 2.0 ** -24], dtype=np.float32)
+    assert O.quantise(q) == [1 << 29, 1 << 28, 1 << 30, 0, 0, 2, (1 << 30) - 64]
+
+
+def test_select_hand_worked_examples():
+    # derived by hand from the rule with rho = 0.5, using t = S - rho (n-1):
+    # q=[.9,.6,.3,.1]: t=.4 -> drop .3 (idx 2); t=1.6-1.0=.6 -> drop idx 1.
+    k = O.quantise(np.array([0.9, 0.6, 0.3, 0.1], np.float32))
+    assert O.select_group(k, 2, 1 << 29) == ([0, 3], [2, 1])
+    # q=[.95,.9,.8,.7,.65,.3,.2,.05]: S=4.55,t=1.05 -> idx0; S=3.6,t=.6 -> idx4 (.65);
+    # S=2.95,t=.45 -> idx5 (.3, dist .15 < .25); S=2.65,t=.65 -> idx3 (.7)
+    k = O.quantise(np.array([0.95, 0.9, 0.8, 0.7, 0.65, 0.3, 0.2, 0.05], np.float32))
+    assert O.select_group(k, 4, 1 << 29) == ([1, 2, 6, 7], [0, 4, 5, 3])
+    # low-probability group: t is below every q for a while, so minima go first
+    k = O.quantise(np.array([0.1, 0.1, 0.2, 0.05, 0.3, 0.15, 0.1, 0.9], np.float32))
+    assert O.select_group(k, 4, 1 << 29) == ([2, 4, 5, 7], [3, 0, 1, 6])
+    # all equal: every step is an exact tie -> lowest index goes
+    k = O.quantise(np.full(8, 0.5, np.float32))
+    assert O.select_group(k, 4, 1 << 29) == ([4, 5, 6, 7], [0, 1, 2, 3])
+
+
+def test_select_lemma_4_1_strict_improvement():
+    # Lemma 4.1: if mu > rho and some q_j > mu (or the mirror case), pruning that j
+    # moves the mean toward rho, by mu_{-j} - mu = (mu - q_j)/(G-1).  The lemma's
+    # proof does not consider a step that jumps past rho (possible for small G), so
+    # the strict decrease is asserted only when that j does not overshoot; the
+    # argmin rule is at least as good as that j.
+    rnd = random.Random(5)
+    hits = 0
+    for _ in range(2000):
+        G = rnd.randint(3, 12)
+        k = [rnd.randint(0, 1 << 30) for _ in range(G)]
+        R = rnd.randint(0, 1 << 30)
+        mu = Fraction(sum(k), G)
+        good = []
+        for j in range(G):
+            mu_j = Fraction(sum(k) - k[j], G - 1)
+            assert mu_j - mu == (mu - k[j]) / (G - 1)
+            if (mu > R and k[j] > mu and mu_j >= R) or (mu < R and k[j] < mu and mu_j <= R):
+                good.append(j)
+        if not good:
+            continue
+        hits += 1
+        live, _ = O.select_group(k, G - 1, R)
+        mu_after = Fraction(sum(k[i] for i in live), G - 1)
+        assert abs(mu_after - R) < abs(mu - R)
+    assert hits > 300
+
+
+def test_select_outputs_exactly_k_sorted_and_group_independent():
+    rng = np.random.default_rng(9)
+    n_groups, G, K = 6, 8, 3
+    p = rng.random(n_groups * G).astype(np.float32)
+    keep, surv = O.select(p, n_groups, G, K, 0.5)
+    assert keep.dtype == np.uint8 and surv.dtype == np.int32
+    assert keep.reshape(n_groups, G).sum(axis=1).tolist() == [K] * n_groups
+    assert np.array_equal(np.flatnonzero(keep), surv)
+    # groups are independent: permuting whole groups permutes the result
+    perm = rng.permutation(n_groups)
+    p2 = p.reshape(n_groups, G)[perm].reshape(-1)
+    keep2, _ = O.select(p2, n_groups, G, K, 0.5)
+    assert np.array_equal(keep2.reshape(n_groups, G), keep.reshape(n_groups, G)[perm])
+    # K == G keeps everything; bad K is rejected
+    keep3, surv3 = O.select(p, n_groups, G, G, 0.5)
+    assert keep3.all() and np.array_equal(surv3, np.arange(n_groups * G))
+    with pytest.raises(ValueError):
+        O.select(p, n_groups, G, 0, 0.5)
+    with pytest.raises(ValueError):
+        O.select(p, n_groups, G, G + 1, 0.5)
+
+
+def test_select_not_worse_than_random_subset_on_average():
+    # sanity, not parity: the greedy rule's |mean - rho| is far below a random K-subset's
+    rng = np.random.default_rng(13)
+    G, K = 16, 8
+    dev_sel, dev_rnd = 0.0, 0.0
+    for _ in range(200):
+        p = rng.beta(0.5, 0.5, G).astype(np.float32)
+        _, surv = O.select(p, 1, G, K, 0.5)
+        dev_sel += abs(float(p[surv].mean()) - 0.5)
+        dev_rnd += abs(float(p[rng.permutation(G)[:K]].mean()) - 0.5)
+    assert dev_sel < 0.5 * dev_rnd
+
+
+# ----------------------------------------------------------------------------- compact
+def make_paged(rng, N, ppr, page_tokens, L=2, H=2, hd=4, seq_lens=None, extra_pages=3, max_len=None):
+    P = N * ppr + extra_pages
+    kv = rng.integers(0, 1 << 16, size=(L, 2, P, page_tokens, H, hd), dtype=np.uint16)
+    bt = rng.permutation(P)[:N * ppr].reshape(N, ppr).astype(np.int32)
+    if seq_lens is None:
+        seq_lens = np.full(N, ppr * page_tokens, np.int32)
+    max_len = max_len or ppr * page_tokens
+    tokens = rng.integers(0, 1000, size=(N, max_len), dtype=np.int32)
+    return kv, bt, np.asarray(seq_lens, np.int32), tokens
+
+
+def test_compact_logical_content_is_preserved():
+    rng = np.random.default_rng(21)
+    N, ppr, pt = 7, 4, 4
+    seq = rng.integers(1, ppr * pt + 1, size=N).astype(np.int32)
+    kv, bt, seq, tok = make_paged(rng, N, ppr, pt, seq_lens=seq)
+    surv = np.array([1, 2, 5, 6], np.int32)
+    out = O.compact(kv, bt, seq, tok, surv, n_pages_dst=len(surv) * ppr)
+    used = 0
+    for r, src in enumerate(surv):
+        assert out["seq_len_dst"][r] == seq[src] and out["src_of_dst"][r] == src
+        assert np.array_equal(out["tokens_dst"][r], tok[src])
+        n_pages = -(-int(seq[src]) // pt)
+        assert out["block_table_dst"][r, :n_pages].tolist() == list(range(used, used + n_pages))
+        assert np.all(out["block_table_dst"][r, n_pages:] == -1)
+        for t in range(int(seq[src])):          # read token t through either table
+            p, o = divmod(t, pt)
+            a = kv[:, :, bt[src, p], o]
+            b = out["kv_dst"][:, :, out["block_table_dst"][r, p], o]
+            assert np.array_equal(a, b)
+        used += n_pages
+    assert out["n_pages_used"] == used
+    # destination pages past n_pages_used are untouched
+    assert np.all(out["kv_dst"][:, :, used:] == 0)
+
+
+def test_compact_equals_library_gather_and_ignores_pruned_pages():
+    rng = np.random.default_rng(22)
+    N, ppr, pt = 8, 3, 2
+    kv, bt, seq, tok = make_paged(rng, N, ppr, pt)
+    surv = np.array([0, 3, 4, 7], np.int32)
+    out = O.compact(kv, bt, seq, tok, surv, n_pages_dst=len(surv) * ppr)
+    flat_src_pages = bt[surv].reshape(-1)
+    assert np.array_equal(out["kv_dst"], np.take(kv, flat_src_pages, axis=2))
+    # poison every page that belongs to no survivor: result must not change
+    kv2 = kv.copy()
+    dead = np.setdiff1d(np.arange(kv.shape[2]), flat_src_pages)
+    kv2[:, :, dead] = 0x7FC0  # bf16 NaN pattern
+    out2 = O.compact(kv2, bt, seq, tok, surv, n_pages_dst=len(surv) * ppr)
+    assert np.array_equal(out2["kv_dst"], out["kv_dst"])
+    assert not np.any(out2["kv_dst"] == 0x7FC0) or np.any(kv[:, :, flat_src_pages] == 0x7FC0)
+
+
+def test_compact_identity_and_page_permutation_invariance():
+    rng = np.random.default_rng(23)
+    N, ppr, pt = 4, 2, 4
+    kv, bt, seq, tok = make_paged(rng, N, ppr, pt, extra_pages=0)
+    dense = np.arange(N * ppr, dtype=np.int32).reshape(N, ppr)
+    out = O.compact(kv, dense, seq, tok, np.arange(N, dtype=np.int32), n_pages_dst=N * ppr)
+    assert np.array_equal(out["kv_dst"], kv) and np.array_equal(out["block_table_dst"], dense)
+    # relabel physical pages: move page p to sigma[p], rewrite the table -> same result
+    surv = np.array([1, 3], np.int32)
+    ref = O.compact(kv, bt, seq, tok, surv, n_pages_dst=4)
+    sigma = rng.permutation(kv.shape[2])
+    kv_perm = np.empty_like(kv)
+    kv_perm[:, :, sigma] = kv
+    out_perm = O.compact(kv_perm, sigma[bt].astype(np.int32), seq, tok, surv, n_pages_dst=4)
+    assert np.array_equal(out_perm["kv_dst"], ref["kv_dst"])
+
+
+# ----------------------------------------------------------------------------- logprob
+def test_logprob_full_distribution_sums_to_one():
+    rng = np.random.default_rng(31)
+    h = f32_to_bf16_bits(rng.standard_normal((6, 16)))
+    W = f32_to_bf16_bits(rng.standard_normal((50, 16)))
+    full, lse = O.log_softmax_rows(h, W)
+    assert np.all(np.abs(np.exp(full).sum(axis=1) - 1.0) < 1e-12)
+    tg = rng.integers(0, 50, 6)
+    lp, lse2 = O.logprob(h, W, tg)
+    assert np.allclose(lp, full[np.arange(6), tg], rtol=0, atol=1e-13)
+    assert np.allclose(lse, lse2, rtol=0, atol=1e-13)
+
+
+def test_logprob_zero_head_is_uniform_and_single_class():
+    rng = np.random.default_rng(32)
+    h = f32_to_bf16_bits(rng.standard_normal((3, 8)))
+    V = 37
+    lp, lse = O.logprob(h, np.zeros((V, 8), np.uint16), np.array([0, 5, 36]))
+    assert np.allclose(lp, -math.log(V), rtol=0, atol=1e-15)
+    assert np.allclose(lse, math.log(V), rtol=0, atol=1e-15)
+    lp1, _ = O.logprob(h, f32_to_bf16_bits(rng.standard_normal((1, 8))), np.zeros(3, int))
+    assert np.all(lp1 == 0.0)
+
+
+def test_logprob_two_class_closed_form():
+    # V = 2: log p(target) = -log(1 + exp(z_other - z_target)) with exact rational logits
+    rng = np.random.default_rng(33)
+    d = 12
+    hb = f32_to_bf16_bits(rng.standard_normal((5, d)))
+    Wb = f32_to_bf16_bits(rng.standard_normal((2, d)))
+    tg = np.array([0, 1, 1, 0, 1])
+    lp, _ = O.logprob(hb, Wb, tg)
+    for t in range(5):
+        z = [float(sum(bits_to_fraction(hb[t, k]) * bits_to_fraction(Wb[v, k]) for k in range(d)))
+             for v in range(2)]
+        expect = -math.log1p(math.exp(z[1 - tg[t]] - z[tg[t]]))
+        assert abs(lp[t] - expect) < 1e-13
+
+
+def test_logprob_pure_python_brute_force():
+    rng = np.random.default_rng(34)
+    T, V, d = 3, 7, 5
+    hb = f32_to_bf16_bits(rng.standard_normal((T, d)))
+    Wb = f32_to_bf16_bits(rng.standard_normal((V, d)))
+    tg = [6, 0, 3]
+    lp, lse = O.logprob(hb, Wb, tg)
+    for t in range(T):
+        z = [float(sum(bits_to_fraction(hb[t, k]) * bits_to_fraction(Wb[v, k]) for k in range(d)))
+             for v in range(V)]
+        denom = math.fsum(math.exp(x) for x in z)
+        assert abs(lp[t] - (z[tg[t]] - math.log(denom))) < 1e-13
+        assert abs(lse[t] - math.log(denom)) < 1e-13
+
+
+def test_logprob_shift_invariance_and_dominant_logit():
+    rng = np.random.default_rng(35)
+    T, V, d = 4, 20, 8
+    h = rng.standard_normal((T, d)).astype(np.float32)
+    W = rng.standard_normal((V, d)).astype(np.float32)
+    tg = rng.integers(0, V, T)
+    lp, lse = O.logprob(f32_to_bf16_bits(h), f32_to_bf16_bits(W), tg)
+    # an extra feature h=1 with the same weight c on every vocab row adds c to every logit
+    h2 = np.concatenate([h, np.ones((T, 1), np.float32)], axis=1)
+    W2 = np.concatenate([W, np.full((V, 1), 3.5, np.float32)], axis=1)
+    lp2, lse2 = O.logprob(f32_to_bf16_bits(h2), f32_to_bf16_bits(W2), tg)
+    assert np.allclose(lp2, lp, rtol=0, atol=1e-12)
+    assert np.allclose(lse2, lse + 3.5, rtol=0, atol=1e-12)
+    # one dominant logit on the target -> log-prob -> 0; on another row -> about -gap
+    hd = np.zeros((1, d), np.float32); hd[0, 0] = 64.0
+    Wd = np.zeros((V, d), np.float32); Wd[4, 0] = 1.0
+    lpd, _ = O.logprob(f32_to_bf16_bits(hd), f32_to_bf16_bits(Wd), [4])
+    assert -1e-20 > lpd[0] > -1e-10 or lpd[0] == 0.0 or abs(lpd[0]) < 1e-10
+    lpo, _ = O.logprob(f32_to_bf16_bits(hd), f32_to_bf16_bits(Wd), [5])
+    assert abs(lpo[0] + 64.0) < 1e-9
+
+
+# ----------------------------------------------------------------------------- vote
+def test_vote_worked_example_and_rank_sum():
+    # q=[.2,.9,.9,.4]: ranks 0, (2+3)/2, (2+3)/2, 1 -> doubled [0,5,5,2]
+    w, tally = O.weighted_vote(np.array([0.2, 0.9, 0.9, 0.4], np.float32), [1, 0, 2, 1], 1, 4, 3)
+    assert tally.tolist() == [[5, 2, 5]] and w.tolist() == [0]   # majority vote would say 1
+    rng = np.random.default_rng(41)
+    for C in [1, 2, 5, 16]:
+        q = rng.integers(0, 6, C).astype(np.float32) / 8  # ties likely
+        ans = rng.integers(0, 4, C)
+        _, t = O.weighted_vote(q, ans, 1, C, 4)
+        assert t.sum() == C * (C - 1)
+
+
+def test_vote_distinct_scores_give_linear_ranks():
+    # no ties: sorted position r has weight r/(C-1) in [0,1]  (rank2 = 2r)
+    q = np.array([0.3, 0.1, 0.8, 0.5, 0.9], np.float32)
+    _, t = O.weighted_vote(q, [0, 1, 2, 3, 4], 1, 5, 5)
+    assert t[0].tolist() == [2, 0, 6, 4, 8]
+    weights = t[0] / (2.0 * (5 - 1))
+    assert weights.min() == 0.0 and weights.max() == 1.0
+
+
+def test_vote_equal_scores_reduce_to_majority():
+    rng = np.random.default_rng(42)
+    for _ in range(50):
+        C, A = 9, 4
+        ans = rng.integers(0, A, C)
+        w, _ = O.weighted_vote(np.full(C, 0.3, np.float32), ans, 1, C, A)
+        counts = np.bincount(ans, minlength=A)
+        assert w[0] == int(np.argmax(counts))       # first max = lowest id on ties
+
+
+def test_vote_invariances_and_single_candidate():
+    rng = np.random.default_rng(43)
+    Q, C, A = 5, 12, 6
+    q = rng.random(Q * C).astype(np.float32)
+    ans = rng.integers(0, A, Q * C)
+    w, t = O.weighted_vote(q, ans, Q, C, A)
+    perm = rng.permutation(C)
+    qp = q.reshape(Q, C)[:, perm].reshape(-1)
+    ap = ans.reshape(Q, C)[:, perm].reshape(-1)
+    w2, t2 = O.weighted_vote(qp, ap, Q, C, A)
+    assert np.array_equal(w, w2) and np.array_equal(t, t2)
+    w3, t3 = O.weighted_vote((q * 4 - 2).astype(np.float32) ** 3, ans, Q, C, A)  # increasing map
+    assert np.array_equal(w, w3) and np.array_equal(t, t3)
+    w1, t1 = O.weighted_vote(np.array([0.7], np.float32), [3], 1, 1, 5)
+    assert w1.tolist() == [3] and t1.sum() == 0      # absent ids never win
