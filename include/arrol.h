@@ -1,0 +1,160 @@
+/*
+ * arrol.h -- C ABI of the ARRoL online rollout-pruning data path for AMD MI355X (gfx950).
+ *
+ * Method: "Prune as You Generate: Online Rollout Pruning for Faster and Better RLVR".
+ * The five calls are the stages of the in-engine pruning path:
+ *   arrol_score          quality head on checkpoint hidden states + sigmoid   (Sec. 4.2, App. A.4)
+ *   arrol_select         exactly-K correctness-balanced survivors per group   (Sec. 4.1, Thm 4.2, App. A.1)
+ *   arrol_compact        gather survivors' paged KV cache / tokens, re-batch  (Sec. 4.3 (i),(ii); Alg. 1)
+ *   arrol_logprob        per-token log pi(o_t | o_<t) on the survivors        (Sec. 3 GRPO ratio; Sec. 4.3 (ii); Alg. 1)
+ *   arrol_weighted_vote  rank-weighted answer vote for test-time scaling      (Sec. 4.4)
+ *
+ * Conventions common to every call
+ *   - Every data pointer is a DEVICE pointer owned by the caller (the library never
+ *     allocates, frees or keeps one).  Scratch memory is passed in as `workspace`;
+ *     its size comes from the matching *_workspace_bytes() query (a host computation).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue kernels on it: no host synchronisation, no device-to-host copy.
+ *   - Return value: ARROL_OK, or a negative ARROL_E* code.  Argument errors are detected
+ *     on the host before anything is launched; on error nothing has been enqueued.
+ *   - Every kernel stays inside the buffers described here for ANY contents of the index
+ *     arrays (out-of-range indices are skipped or clamped, see each call).
+ */
+#ifndef ARROL_H
+#define ARROL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ARROL_OK 0
+#define ARROL_EINVAL (-1)     /* null pointer, bad shape, misaligned base */
+#define ARROL_EWORKSPACE (-2) /* workspace missing or too small */
+#define ARROL_EHIP (-3)       /* the HIP runtime refused a launch */
+
+#define ARROL_MAX_GROUP 64      /* largest G (arrol_select) and C (arrol_weighted_vote) */
+#define ARROL_FIXED_POINT_BITS 30
+
+/* Library version (major*10000 + minor*100 + patch). */
+int arrol_version(void);
+/* Static, NUL-terminated description of a return code. */
+const char* arrol_error_string(int code);
+
+/*
+ * Stage 1 -- quality head and success probability (Sec. 4.2 "Quality Score Prediction";
+ * App. A.4: the score is squashed to [0,1] with the sigmoid).
+ *   s_i = <w, h_i> + bias,  q_i = 1 / (1 + exp(-s_i))
+ * hidden     bf16 [*, d], row r starts at hidden + r*row_stride_elems (elements);
+ *            row_stride_elems >= d and a multiple of 8; base 16-byte aligned.
+ * row_index  NULL, or int64 [n_rows]: output i reads row row_index[i] (lets the caller
+ *            point into a token-major buffer); NULL means row i.
+ * w          fp32 [d]; bias fp32 by value.  d must be a multiple of 8, d >= 8.
+ * score_out  NULL or fp32 [n_rows] (s_i); prob_out fp32 [n_rows] (q_i).
+ * fp32 accumulation of exact bf16 x fp32 products.  n_rows == 0 is a no-op.
+ */
+int arrol_score(const void* hidden, int64_t row_stride_elems, const int64_t* row_index,
+                const float* w, float bias, int32_t n_rows, int32_t d,
+                float* score_out, float* prob_out, void* stream);
+
+/*
+ * Stage 2 -- per-group keep-K selection by the balance rule (Thm 4.2 / App. A.1):
+ * with live set A, mu_{-j} = mean of q_i over A \ {j}; prune argmin_j |mu_{-j} - rho|;
+ * repeat on the shrunken group until K remain.  Decisions are taken on integers
+ * k_i = rint(q_i * 2^30) (round-half-even of the fp32 value) and R = rint(rho * 2^30),
+ * so the result is the same on any hardware; ties prune the lowest index.
+ * prob          fp32 [n_groups*G], finite, in [0,1]; groups are consecutive runs of G.
+ * keep_mask     uint8 [n_groups*G]  1 = survivor.
+ * survivor_idx  int32 [n_groups*K]  global rollout ids, ascending.
+ * Requires 1 <= K <= G <= ARROL_MAX_GROUP.  n_groups == 0 is a no-op.
+ */
+int arrol_select(const float* prob, int32_t n_groups, int32_t G, int32_t K, float rho,
+                 uint8_t* keep_mask, int32_t* survivor_idx, void* stream);
+
+/*
+ * Paged KV pool geometry.  Memory order is [layer][K|V][page][token][kv_head][dim], bf16,
+ * i.e. one (layer, K|V, page) chunk is page_tokens*n_kv_heads*head_dim*2 contiguous bytes.
+ */
+typedef struct arrol_kv_layout {
+    int32_t n_layers;
+    int32_t page_tokens;
+    int32_t n_kv_heads;
+    int32_t head_dim;
+    int64_t n_pages; /* pages per (layer, K|V) slab in THIS pool */
+} arrol_kv_layout;
+
+/*
+ * Stage 3 -- compaction / re-batch (Sec. 4.3 (i): pruned requests leave the pool so their
+ * capacity is reused; (ii) and Alg. 1 "Filter pruned rollouts, rebatch").
+ * Survivor rank r (r-th entry of survivor_idx, source rollout s) owns
+ * np_r = min(ceil(seq_len_src[s] / page_tokens), max_pages_per_seq) destination pages
+ * starting at base_r = sum_{r' < r} np_r'.  For every layer and K|V the source page
+ * block_table_src[s][p] is copied verbatim (whole page) to destination page base_r + p.
+ *   block_table_dst[r][p] = base_r + p (p < np_r), -1 otherwise;  seq_len_dst[r] = seq_len_src[s];
+ *   tokens_dst[r][:] = tokens_src[s][:];  src_of_dst[r] = s;  *n_pages_used = base_{n_keep}.
+ * Source and destination pools must agree in everything but n_pages and must not overlap.
+ * The chunk size (bytes) must be a multiple of 16 and both pool bases 16-byte aligned.
+ * A survivor id outside [0, n_src) gives an empty destination rollout (np_r = 0, seq_len 0,
+ * src_of_dst -1, tokens row of zeros); a source page id outside [0, src.n_pages) or a
+ * destination page >= dst.n_pages is skipped (the caller can detect overflow from
+ * *n_pages_used > dst.n_pages).  Destination pages >= *n_pages_used are left untouched.
+ * tokens_src/tokens_dst may both be NULL (max_len ignored).  n_keep == 0 only writes
+ * *n_pages_used = 0.
+ * workspace: arrol_compact_workspace_bytes(n_keep) bytes, 16-byte aligned.
+ */
+size_t arrol_compact_workspace_bytes(int32_t n_keep);
+int arrol_compact(const void* kv_src, arrol_kv_layout src, void* kv_dst, arrol_kv_layout dst,
+                  const int32_t* block_table_src, const int32_t* seq_len_src,
+                  int32_t max_pages_per_seq, const int32_t* tokens_src, int32_t max_len,
+                  const int32_t* survivor_idx, int32_t n_src, int32_t n_keep,
+                  int32_t* block_table_dst, int32_t* seq_len_dst, int32_t* tokens_dst,
+                  int32_t* src_of_dst, int64_t* n_pages_used,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Stage 4 -- per-token log-probability of the sampled token (the policy term of GRPO's
+ * importance ratio, Sec. 3; computed on the re-batched survivors, Sec. 4.3 (ii), Alg. 1):
+ *   z_t = W h_t,  logprob_t = z_t[y_t] - logsumexp_v z_t[v]      (temperature 1, no bias)
+ * hidden   bf16 [T, d] packed rows (ragged survivors concatenated), 16-byte aligned.
+ * lm_head  bf16 [V, d] row-major, 16-byte aligned.   d multiple of 8, d >= 8; V >= 1.
+ * targets  int32 [T]; a target outside [0, V) yields NaN in logprob_out for that row.
+ * logprob_out fp32 [T];  lse_out NULL or fp32 [T] (the logsumexp).
+ * bf16 products accumulated in fp32 on the matrix cores; the [T, V] logits are never
+ * written to memory.  T == 0 is a no-op.
+ * workspace: arrol_logprob_workspace_bytes(T, V, d) bytes, 16-byte aligned.
+ */
+size_t arrol_logprob_workspace_bytes(int64_t T, int32_t V, int32_t d);
+int arrol_logprob(const void* hidden, const void* lm_head, const int32_t* targets,
+                  int64_t T, int32_t V, int32_t d, float* logprob_out, float* lse_out,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Stage 5 -- rank-weighted vote (Sec. 4.4: candidates are sorted by head score and their
+ * ranks rescaled linearly to [0,1]; the weights replace the unit votes of a majority vote).
+ * Per question with candidates i < C:
+ *   rank2_i = 2*#{j: q_j < q_i} + #{j != i: q_j == q_i}   (twice the average rank; weight = rank2/(2(C-1)))
+ *   tally[a] = sum of rank2_i over candidates with answer a
+ *   winner   = answer id with the largest tally among ids that occur, lowest id on ties
+ * prob       fp32 [n_questions*C] (any monotone score; finite)
+ * answer_id  int32 [n_questions*C]; ids outside [0, n_answers) take no part (a question
+ *            whose ids are all outside gets winner -1).
+ * winner     int32 [n_questions];  tally NULL or int64 [n_questions, n_answers].
+ * Requires 1 <= C <= ARROL_MAX_GROUP, n_answers >= 1.
+ */
+int arrol_weighted_vote(const float* prob, const int32_t* answer_id, int32_t n_questions,
+                        int32_t C, int32_t n_answers, int32_t* winner, int64_t* tally,
+                        void* stream);
+
+/*
+ * Benchmarking knob, not a stage of the method.  key "logprob_splits": number of vocabulary
+ * splits arrol_logprob uses (0 = built-in heuristic).  Process-wide, not thread-safe; the
+ * workspace size must be queried again after changing it.  Unknown key: ARROL_EINVAL.
+ */
+int arrol_set_tuning(const char* key, int value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ARROL_H */

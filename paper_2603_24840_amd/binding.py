@@ -1,0 +1,222 @@
+"""Thin ctypes binding over libarrol.so (the C ABI declared in include/arrol.h).
+
+Argument marshalling only: every stage runs in the library's HIP kernels.  torch is used
+for device memory and streams.  There is no CPU fallback: if the library is missing or a
+tensor is not on the GPU the call raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "lib", "libarrol.so")
+
+OK, EINVAL, EWORKSPACE, EHIP = 0, -1, -2, -3
+MAX_GROUP = 64
+
+
+class ArrolError(RuntimeError):
+    def __init__(self, fn, code):
+        self.code = code
+        super().__init__("%s failed: %s (%d)" % (fn, error_string(code), code))
+
+
+class KVLayout(ctypes.Structure):
+    """Geometry of a paged KV pool: [layer][K|V][page][token][kv_head][dim], bf16."""
+    _fields_ = [("n_layers", ctypes.c_int32), ("page_tokens", ctypes.c_int32),
+                ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("n_pages", ctypes.c_int64)]
+
+
+_lib = None
+
+_vp, _i32, _i64, _f32, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
+_SIGNATURES = {
+    "arrol_version": (ctypes.c_int, []),
+    "arrol_error_string": (ctypes.c_char_p, [ctypes.c_int]),
+    "arrol_set_tuning": (ctypes.c_int, [ctypes.c_char_p, ctypes.c_int]),
+    "arrol_score": (ctypes.c_int, [_vp, _i64, _vp, _vp, _f32, _i32, _i32, _vp, _vp, _vp]),
+    "arrol_select": (ctypes.c_int, [_vp, _i32, _i32, _i32, _f32, _vp, _vp, _vp]),
+    "arrol_compact_workspace_bytes": (_sz, [_i32]),
+    "arrol_compact": (ctypes.c_int, [_vp, KVLayout, _vp, KVLayout, _vp, _vp, _i32, _vp, _i32, _vp, _i32, _i32,
+                                     _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "arrol_logprob_workspace_bytes": (_sz, [_i64, _i32, _i32]),
+    "arrol_logprob": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
+    "arrol_weighted_vote": (ctypes.c_int, [_vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp]),
+}
+
+
+def lib():
+    """Loads libarrol.so once; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libarrol.so is not built (%s missing): run "
+                               "`python -m paper_2603_24840_amd.build`; there is no fallback path" % LIB_PATH)
+        handle = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = handle
+    return _lib
+
+
+def version():
+    return lib().arrol_version()
+
+
+def error_string(code):
+    return lib().arrol_error_string(code).decode()
+
+
+def set_tuning(key, value):
+    rc = lib().arrol_set_tuning(key.encode(), int(value))
+    if rc != OK:
+        raise ArrolError("arrol_set_tuning", rc)
+
+
+def _ptr(t, dtype=None, name="tensor"):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("%s must live on the GPU: the ARRoL path has no CPU implementation" % name)
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError("%s must be %s, got %s" % (name, dtype, t.dtype))
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    return t.data_ptr()
+
+
+def _stream(stream):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return s.cuda_stream
+
+
+def _check(fn, rc):
+    if rc != OK:
+        raise ArrolError(fn, rc)
+
+
+def arrol_score(hidden, w, bias=0.0, row_index=None, out_score=None, out_prob=None, stream=None):
+    """hidden bf16 [R, d] (rows may be strided), w fp32 [d] -> (score fp32 [n], prob fp32 [n])."""
+    if hidden.dim() != 2 or hidden.dtype != torch.bfloat16 or not hidden.is_cuda:
+        raise TypeError("hidden must be a 2-D bf16 GPU tensor")
+    if hidden.stride(1) != 1:
+        raise ValueError("hidden rows must be contiguous")
+    d = hidden.shape[1]
+    n = hidden.shape[0] if row_index is None else row_index.numel()
+    dev = hidden.device
+    if out_score is None:
+        out_score = torch.empty(n, dtype=torch.float32, device=dev)
+    if out_prob is None:
+        out_prob = torch.empty(n, dtype=torch.float32, device=dev)
+    row_stride = hidden.stride(0) if hidden.shape[0] > 1 else max(d, hidden.stride(0))
+    rc = lib().arrol_score(hidden.data_ptr(), row_stride, _ptr(row_index, torch.int64, "row_index"),
+                           _ptr(w, torch.float32, "w"), float(bias), n, d,
+                           _ptr(out_score, torch.float32, "out_score"), _ptr(out_prob, torch.float32, "out_prob"),
+                           _stream(stream))
+    _check("arrol_score", rc)
+    return out_score, out_prob
+
+
+def arrol_select(prob, n_groups, G, K, rho=0.5, out_keep=None, out_survivors=None, stream=None):
+    """prob fp32 [n_groups*G] -> (keep_mask uint8 [n_groups*G], survivor_idx int32 [n_groups*K])."""
+    dev = prob.device
+    if prob.numel() != n_groups * G:
+        raise ValueError("prob must have n_groups*G entries")
+    if out_keep is None:
+        out_keep = torch.empty(n_groups * G, dtype=torch.uint8, device=dev)
+    if out_survivors is None:
+        out_survivors = torch.empty(max(0, n_groups * K), dtype=torch.int32, device=dev)
+    rc = lib().arrol_select(_ptr(prob, torch.float32, "prob"), n_groups, G, K, float(rho),
+                            _ptr(out_keep, torch.uint8, "keep_mask"), _ptr(out_survivors, torch.int32, "survivor_idx"),
+                            _stream(stream))
+    _check("arrol_select", rc)
+    return out_keep, out_survivors
+
+
+def kv_layout_of(kv):
+    """KVLayout of a [L, 2, P, page_tokens, H_kv, hd] bf16 tensor."""
+    if kv.dim() != 6 or kv.shape[1] != 2:
+        raise ValueError("KV pool must be [layers, 2, pages, page_tokens, kv_heads, head_dim]")
+    L, _, P, pt, H, hd = kv.shape
+    return KVLayout(L, pt, H, hd, P)
+
+
+def arrol_compact_workspace_bytes(n_keep):
+    return lib().arrol_compact_workspace_bytes(n_keep)
+
+
+def arrol_compact(kv_src, kv_dst, block_table_src, seq_len_src, tokens_src, survivor_idx,
+                  out=None, workspace=None, stream=None):
+    """Gathers survivors into kv_dst (written in place).  Returns a dict with block_table_dst,
+    seq_len_dst, tokens_dst, src_of_dst, n_pages_used (device int64 scalar tensor)."""
+    dev = kv_src.device
+    n_src, ppr = block_table_src.shape
+    n_keep = survivor_idx.numel()
+    max_len = tokens_src.shape[1] if tokens_src is not None else 0
+    if out is None:
+        out = dict(
+            block_table_dst=torch.empty((n_keep, ppr), dtype=torch.int32, device=dev),
+            seq_len_dst=torch.empty(n_keep, dtype=torch.int32, device=dev),
+            tokens_dst=(torch.empty((n_keep, max_len), dtype=torch.int32, device=dev)
+                        if tokens_src is not None else None),
+            src_of_dst=torch.empty(n_keep, dtype=torch.int32, device=dev),
+            n_pages_used=torch.empty(1, dtype=torch.int64, device=dev))
+    need = arrol_compact_workspace_bytes(n_keep)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+    rc = lib().arrol_compact(
+        _ptr(kv_src, torch.bfloat16, "kv_src"), kv_layout_of(kv_src),
+        _ptr(kv_dst, torch.bfloat16, "kv_dst"), kv_layout_of(kv_dst),
+        _ptr(block_table_src, torch.int32, "block_table_src"), _ptr(seq_len_src, torch.int32, "seq_len_src"),
+        ppr, _ptr(tokens_src, torch.int32, "tokens_src"), max_len,
+        _ptr(survivor_idx, torch.int32, "survivor_idx"), n_src, n_keep,
+        _ptr(out["block_table_dst"], torch.int32, "block_table_dst"), _ptr(out["seq_len_dst"], torch.int32, "seq_len_dst"),
+        _ptr(out["tokens_dst"], torch.int32, "tokens_dst"), _ptr(out["src_of_dst"], torch.int32, "src_of_dst"),
+        _ptr(out["n_pages_used"], torch.int64, "n_pages_used"),
+        _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
+    _check("arrol_compact", rc)
+    return out
+
+
+def arrol_logprob_workspace_bytes(T, V, d):
+    return lib().arrol_logprob_workspace_bytes(T, V, d)
+
+
+def arrol_logprob(hidden, lm_head, targets, out_logprob=None, out_lse=None, want_lse=False,
+                  workspace=None, stream=None):
+    """hidden bf16 [T, d], lm_head bf16 [V, d], targets int32 [T] -> logprob fp32 [T] (and lse)."""
+    T, d = hidden.shape
+    V = lm_head.shape[0]
+    if lm_head.shape[1] != d:
+        raise ValueError("hidden and lm_head disagree on d")
+    dev = hidden.device
+    if out_logprob is None:
+        out_logprob = torch.empty(T, dtype=torch.float32, device=dev)
+    if out_lse is None and want_lse:
+        out_lse = torch.empty(T, dtype=torch.float32, device=dev)
+    need = arrol_logprob_workspace_bytes(T, V, d)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+    rc = lib().arrol_logprob(_ptr(hidden, torch.bfloat16, "hidden"), _ptr(lm_head, torch.bfloat16, "lm_head"),
+                             _ptr(targets, torch.int32, "targets"), T, V, d,
+                             _ptr(out_logprob, torch.float32, "logprob_out"), _ptr(out_lse, torch.float32, "lse_out"),
+                             _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
+    _check("arrol_logprob", rc)
+    return (out_logprob, out_lse) if (want_lse or out_lse is not None) else out_logprob
+
+
+def arrol_weighted_vote(prob, answer_id, n_questions, C, n_answers, want_tally=False, stream=None):
+    """prob fp32 [Q*C], answer_id int32 [Q*C] -> winner int32 [Q] (and tally int64 [Q, A])."""
+    dev = prob.device
+    if prob.numel() != n_questions * C or answer_id.numel() != n_questions * C:
+        raise ValueError("prob and answer_id must have n_questions*C entries")
+    winner = torch.empty(n_questions, dtype=torch.int32, device=dev)
+    tally = torch.empty((n_questions, n_answers), dtype=torch.int64, device=dev) if want_tally else None
+    rc = lib().arrol_weighted_vote(_ptr(prob, torch.float32, "prob"), _ptr(answer_id, torch.int32, "answer_id"),
+                                   n_questions, C, n_answers, _ptr(winner, torch.int32, "winner"),
+                                   _ptr(tally, torch.int64, "tally"), _stream(stream))
+    _check("arrol_weighted_vote", rc)
+    return (winner, tally) if want_tally else winner

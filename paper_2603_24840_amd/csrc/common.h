@@ -1,0 +1,50 @@
+// Shared host/device helpers for the ARRoL HIP library (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "arrol.h"
+
+#define ARROL_WAVE 64
+
+// 16-byte native vector (the nontemporal builtins need a native vector, not HIP's uint4 class)
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+static inline int arrol_launch_status() {
+    return hipGetLastError() == hipSuccess ? ARROL_OK : ARROL_EHIP;
+}
+
+static inline bool arrol_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// 64-bit lane exchange built from two 32-bit shuffles.
+__device__ __forceinline__ int64_t shfl_xor_i64(int64_t v, int mask) {
+    int lo = __shfl_xor(static_cast<int>(v & 0xffffffffll), mask, ARROL_WAVE);
+    int hi = __shfl_xor(static_cast<int>(v >> 32), mask, ARROL_WAVE);
+    return (static_cast<int64_t>(hi) << 32) | static_cast<uint32_t>(lo);
+}
+__device__ __forceinline__ int64_t shfl_i64(int64_t v, int src) {
+    int lo = __shfl(static_cast<int>(v & 0xffffffffll), src, ARROL_WAVE);
+    int hi = __shfl(static_cast<int>(v >> 32), src, ARROL_WAVE);
+    return (static_cast<int64_t>(hi) << 32) | static_cast<uint32_t>(lo);
+}
+__device__ __forceinline__ int64_t wave_sum_i64(int64_t v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += shfl_xor_i64(v, m);
+    return v;
+}
+__device__ __forceinline__ int64_t wave_min_i64(int64_t v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) { int64_t o = shfl_xor_i64(v, m); v = o < v ? o : v; }
+    return v;
+}
+__device__ __forceinline__ int64_t wave_max_i64(int64_t v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) { int64_t o = shfl_xor_i64(v, m); v = o > v ? o : v; }
+    return v;
+}
+__device__ __forceinline__ float wave_sum_f32(float v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, ARROL_WAVE);
+    return v;
+}
+__device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }

@@ -1,0 +1,181 @@
+// arrol_compact: gather the survivors' paged KV cache, block tables and token buffers into a
+// dense destination pool (Sec. 4.3 (i): pruned requests leave the pool and their capacity is
+// reused; (ii) / Alg. 1: survivors are filtered and re-batched).
+//
+// Two launches on the caller's stream, no host round trip:
+//   plan  one workgroup: pages per survivor, exclusive prefix scan (wave scan + LDS carry),
+//         destination block tables / lengths / source map / page count.
+//   copy  HBM streaming: one workgroup per (layer, K|V, survivor, logical page) chunk, every
+//         lane moving 16 bytes per access with all loads of a chunk issued before its stores;
+//         extra workgroups move the token rows.
+#include "common.h"
+
+namespace {
+
+constexpr int kPlanThreads = 1024;
+constexpr int kCopyThreads = 256;
+constexpr int kCopyUnroll = 8;  // 16-byte accesses in flight per lane
+
+__device__ __forceinline__ int pages_of(const int32_t* seq_len_src, int src, int n_src, int page_tokens, int ppr) {
+    if (src < 0 || src >= n_src) return 0;
+    const int len = seq_len_src[src];
+    if (len <= 0) return 0;
+    const int np = (len - 1) / page_tokens + 1;
+    return np < ppr ? np : ppr;
+}
+
+// workspace layout: int32 base[n_keep + 1]
+__global__ __launch_bounds__(kPlanThreads) void compact_plan_kernel(
+    const int32_t* __restrict__ survivor_idx, const int32_t* __restrict__ seq_len_src, int n_src, int n_keep,
+    int page_tokens, int ppr, int32_t* __restrict__ base, int32_t* __restrict__ block_table_dst,
+    int32_t* __restrict__ seq_len_dst, int32_t* __restrict__ src_of_dst, int64_t* __restrict__ n_pages_used) {
+    __shared__ int wave_tot[kPlanThreads / ARROL_WAVE];
+    __shared__ int carry_s;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) carry_s = 0;
+    __syncthreads();
+    for (int r0 = 0; r0 < n_keep; r0 += kPlanThreads) {
+        const int r = r0 + tid;
+        int src = -1, np = 0;
+        if (r < n_keep) {
+            src = survivor_idx[r];
+            np = pages_of(seq_len_src, src, n_src, page_tokens, ppr);
+        }
+        int incl = np;  // inclusive scan inside the wave
+#pragma unroll
+        for (int o = 1; o < ARROL_WAVE; o <<= 1) {
+            const int v = __shfl_up(incl, o, ARROL_WAVE);
+            if (lane >= o) incl += v;
+        }
+        if (lane == 63) wave_tot[wave] = incl;
+        __syncthreads();
+        int before = carry_s;
+        for (int wv = 0; wv < wave; ++wv) before += wave_tot[wv];
+        const int excl = before + incl - np;
+        if (r < n_keep) {
+            const bool valid = src >= 0 && src < n_src;
+            base[r] = excl;
+            seq_len_dst[r] = valid ? seq_len_src[src] : 0;
+            src_of_dst[r] = valid ? src : -1;
+        }
+        __syncthreads();
+        if (tid == kPlanThreads - 1) carry_s = excl + np;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        base[n_keep] = carry_s;
+        *n_pages_used = carry_s;
+    }
+    // block tables: base[] was written by this workgroup; make it visible, then fill rows
+    __syncthreads();
+    const int64_t total = static_cast<int64_t>(n_keep) * ppr;
+    for (int64_t i = tid; i < total; i += kPlanThreads) {
+        const int r = static_cast<int>(i / ppr), p = static_cast<int>(i % ppr);
+        const int np = base[r + 1] - base[r];
+        block_table_dst[i] = p < np ? base[r] + p : -1;
+    }
+}
+
+__global__ __launch_bounds__(kCopyThreads) void compact_copy_kernel(
+    const u32x4* __restrict__ kv_src, u32x4* __restrict__ kv_dst, int64_t chunk_vec, int64_t src_pages,
+    int64_t dst_pages, const int32_t* __restrict__ block_table_src, const int32_t* __restrict__ survivor_idx,
+    const int32_t* __restrict__ base, int n_src, int n_keep, int ppr, int64_t kv_blocks,
+    const int32_t* __restrict__ tokens_src, int32_t* __restrict__ tokens_dst, int max_len) {
+    const int64_t bid = blockIdx.x;
+    if (bid < kv_blocks) {
+        // bid = slab * (n_keep * ppr) + r * ppr + p : consecutive workgroups write consecutive pages
+        const int64_t slots = static_cast<int64_t>(n_keep) * ppr;
+        const int64_t slab = bid / slots;
+        const int64_t slot = bid - slab * slots;
+        const int r = static_cast<int>(slot / ppr), p = static_cast<int>(slot - static_cast<int64_t>(r) * ppr);
+        const int b0 = base[r];
+        if (p >= base[r + 1] - b0) return;
+        const int src = survivor_idx[r];  // valid: the plan gave this survivor pages
+        const int64_t sp = block_table_src[static_cast<int64_t>(src) * ppr + p];
+        const int64_t dp = static_cast<int64_t>(b0) + p;
+        if (sp < 0 || sp >= src_pages || dp >= dst_pages) return;
+        const u32x4* s = kv_src + (slab * src_pages + sp) * chunk_vec;
+        u32x4* d = kv_dst + (slab * dst_pages + dp) * chunk_vec;
+        for (int64_t v0 = 0; v0 < chunk_vec; v0 += kCopyThreads * kCopyUnroll) {
+            u32x4 x[kCopyUnroll];
+#pragma unroll
+            for (int u = 0; u < kCopyUnroll; ++u) {
+                const int64_t v = v0 + u * kCopyThreads + threadIdx.x;
+                if (v < chunk_vec) x[u] = __builtin_nontemporal_load(s + v);
+            }
+#pragma unroll
+            for (int u = 0; u < kCopyUnroll; ++u) {
+                const int64_t v = v0 + u * kCopyThreads + threadIdx.x;
+                if (v < chunk_vec) __builtin_nontemporal_store(x[u], d + v);
+            }
+        }
+    } else {
+        const int r = static_cast<int>(bid - kv_blocks);
+        const int src = survivor_idx[r];
+        const bool valid = src >= 0 && src < n_src;
+        const int32_t* s = tokens_src + static_cast<int64_t>(valid ? src : 0) * max_len;
+        int32_t* d = tokens_dst + static_cast<int64_t>(r) * max_len;
+        for (int i = threadIdx.x; i < max_len; i += kCopyThreads) d[i] = valid ? s[i] : 0;
+    }
+}
+
+__global__ void compact_empty_kernel(int64_t* n_pages_used) { *n_pages_used = 0; }
+
+bool same_geometry(const arrol_kv_layout& a, const arrol_kv_layout& b) {
+    return a.n_layers == b.n_layers && a.page_tokens == b.page_tokens && a.n_kv_heads == b.n_kv_heads &&
+           a.head_dim == b.head_dim;
+}
+
+}  // namespace
+
+extern "C" size_t arrol_compact_workspace_bytes(int32_t n_keep) {
+    if (n_keep < 0) return 0;
+    return ((static_cast<size_t>(n_keep) + 1) * sizeof(int32_t) + 255) & ~static_cast<size_t>(255);
+}
+
+extern "C" int arrol_compact(const void* kv_src, arrol_kv_layout src, void* kv_dst, arrol_kv_layout dst,
+                             const int32_t* block_table_src, const int32_t* seq_len_src,
+                             int32_t max_pages_per_seq, const int32_t* tokens_src, int32_t max_len,
+                             const int32_t* survivor_idx, int32_t n_src, int32_t n_keep,
+                             int32_t* block_table_dst, int32_t* seq_len_dst, int32_t* tokens_dst,
+                             int32_t* src_of_dst, int64_t* n_pages_used,
+                             void* workspace, size_t workspace_bytes, void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (n_keep < 0 || n_src < 0 || !n_pages_used) return ARROL_EINVAL;
+    if (n_keep == 0) {
+        hipLaunchKernelGGL(compact_empty_kernel, dim3(1), dim3(1), 0, st, n_pages_used);
+        return arrol_launch_status();
+    }
+    if (!same_geometry(src, dst) || src.n_layers < 1 || src.page_tokens < 1 || src.n_kv_heads < 1 ||
+        src.head_dim < 1 || src.n_pages < 0 || dst.n_pages < 0 || max_pages_per_seq < 1)
+        return ARROL_EINVAL;
+    const int64_t chunk_bytes = static_cast<int64_t>(src.page_tokens) * src.n_kv_heads * src.head_dim * 2;
+    if (chunk_bytes % 16) return ARROL_EINVAL;
+    if (!kv_src || !kv_dst || !block_table_src || !seq_len_src || !survivor_idx || !block_table_dst ||
+        !seq_len_dst || !src_of_dst || !arrol_aligned16(kv_src) || !arrol_aligned16(kv_dst))
+        return ARROL_EINVAL;
+    const bool with_tokens = tokens_src != nullptr || tokens_dst != nullptr;
+    if (with_tokens && (!tokens_src || !tokens_dst || max_len < 0)) return ARROL_EINVAL;
+    // the pools may not overlap
+    const char* a0 = static_cast<const char*>(kv_src);
+    const char* b0 = static_cast<const char*>(kv_dst);
+    const int64_t a_len = chunk_bytes * src.n_pages * src.n_layers * 2, b_len = chunk_bytes * dst.n_pages * dst.n_layers * 2;
+    if (a0 < b0 + b_len && b0 < a0 + a_len) return ARROL_EINVAL;
+    if (!workspace || !arrol_aligned16(workspace) || workspace_bytes < arrol_compact_workspace_bytes(n_keep))
+        return ARROL_EWORKSPACE;
+    const int64_t slots = static_cast<int64_t>(n_keep) * max_pages_per_seq;
+    if (slots > INT32_MAX) return ARROL_EINVAL;  // page ids are int32
+    const int64_t kv_blocks = slots * src.n_layers * 2;
+    const int64_t blocks = kv_blocks + (with_tokens && max_len > 0 ? n_keep : 0);
+    if (blocks > INT32_MAX) return ARROL_EINVAL;
+    int32_t* base = static_cast<int32_t*>(workspace);
+    hipLaunchKernelGGL(compact_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, survivor_idx, seq_len_src, n_src,
+                       n_keep, src.page_tokens, max_pages_per_seq, base, block_table_dst, seq_len_dst, src_of_dst,
+                       n_pages_used);
+    if (hipGetLastError() != hipSuccess) return ARROL_EHIP;
+    hipLaunchKernelGGL(compact_copy_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kCopyThreads), 0, st,
+                       static_cast<const u32x4*>(kv_src), static_cast<u32x4*>(kv_dst), chunk_bytes / 16,
+                       src.n_pages, dst.n_pages, block_table_src, survivor_idx, base, n_src, n_keep,
+                       max_pages_per_seq, kv_blocks, tokens_src, tokens_dst, max_len);
+    return arrol_launch_status();
+}

@@ -1,0 +1,149 @@
+"""Seeded synthetic inputs shaped like the paper's 1B-8B Qwen-3 / LLaMA-3.2 workloads.
+
+Input generation only: nothing of the method's arithmetic lives here.  Both the HIP
+path and the CPU oracle are fed from these generators (tensors are produced once, on the
+requested device, and copied to the host for the oracle).
+"""
+from dataclasses import dataclass, replace
+
+import torch
+
+BASE_SEED = 260324840
+
+
+@dataclass(frozen=True)
+class Config:
+    name: str
+    index: int
+    n_prompts: int          # B
+    G: int                  # rollouts per prompt
+    K: int                  # kept per prompt
+    d: int                  # hidden size
+    ckpt_len: int           # tokens in cache at the pruning checkpoint (L_detect)
+    n_layers: int
+    n_kv_heads: int
+    head_dim: int
+    page_tokens: int
+    vocab: int
+    resp_lo: int            # survivor response lengths ~ U[resp_lo, resp_hi]
+    resp_hi: int
+    vote_q: int             # test-time vote: questions, candidates, answer ids
+    vote_c: int
+    vote_a: int
+    rho: float = 0.5
+
+    @property
+    def n_rollouts(self):
+        return self.n_prompts * self.G
+
+    @property
+    def n_keep(self):
+        return self.n_prompts * self.K
+
+    @property
+    def pages_per_rollout(self):
+        return -(-self.ckpt_len // self.page_tokens)
+
+    @property
+    def chunk_bytes(self):
+        return self.page_tokens * self.n_kv_heads * self.head_dim * 2
+
+
+CONFIGS = {
+    "tiny": Config("tiny", 0, 4, 8, 4, 256, 64, 2, 2, 64, 16, 4096, 128, 128, 1, 8, 4),
+    "llama1b": Config("llama1b", 1, 64, 8, 4, 2048, 512, 16, 8, 64, 16, 128256, 256, 2048, 64, 8, 16),
+    "qwen1p7b": Config("qwen1p7b", 2, 128, 8, 4, 2048, 1024, 28, 8, 128, 16, 151936, 512, 4096, 128, 8, 16),
+    "llama3b": Config("llama3b", 3, 64, 16, 8, 3072, 1024, 28, 8, 128, 16, 128256, 512, 4096, 64, 16, 16),
+    "qwen8b": Config("qwen8b", 4, 64, 16, 8, 4096, 1024, 36, 8, 128, 16, 151936, 1024, 8192, 512, 64, 16),
+}
+
+
+def shrink(cfg, **kw):
+    """A copy of cfg with some fields replaced (used for reduced-size parity cases)."""
+    return replace(cfg, **kw)
+
+
+def _gen(cfg, stage, device):
+    g = torch.Generator(device=device)
+    g.manual_seed(BASE_SEED + 1000 * cfg.index + stage)
+    return g
+
+
+def randn_bf16(shape, gen, device, std=1.0, slab=1 << 26):
+    """bf16 ~ N(0, std^2), generated in fp32 slabs to bound the temporary."""
+    out = torch.empty(shape, dtype=torch.bfloat16, device=device)
+    flat = out.view(-1)
+    n = flat.numel()
+    for s in range(0, n, slab):
+        e = min(n, s + slab)
+        tmp = torch.randn(e - s, generator=gen, device=device, dtype=torch.float32)
+        if std != 1.0:
+            tmp.mul_(std)
+        flat[s:e] = tmp.to(torch.bfloat16)
+    return out
+
+
+def score_inputs(cfg, device, n_rows=None):
+    """Checkpoint hidden states [N, d] bf16 ~ N(0,1); head weights fp32 ~ N(0, 1/d); bias 0."""
+    g = _gen(cfg, 1, device)
+    n = cfg.n_rollouts if n_rows is None else n_rows
+    hidden = randn_bf16((n, cfg.d), g, device)
+    w = torch.randn(cfg.d, generator=g, device=device, dtype=torch.float32) * (cfg.d ** -0.5)
+    return hidden, w, 0.0
+
+
+def select_inputs(cfg, device):
+    """Probabilities as the sigmoid of N(0,1) scores (what stage 1 yields at these shapes)."""
+    g = _gen(cfg, 2, device)
+    s = torch.randn(cfg.n_rollouts, generator=g, device=device, dtype=torch.float32)
+    return torch.sigmoid(s)
+
+
+def compact_inputs(cfg, device, extra_pages=0, ragged=False, n_layers=None):
+    """Paged KV pool bf16 ~ N(0,1); block tables = one random permutation of all pages cut into
+    rows; every rollout holds ckpt_len tokens (ragged=True draws lengths in [1, ckpt_len]);
+    token ids uniform over the vocabulary."""
+    g = _gen(cfg, 3, device)
+    L = cfg.n_layers if n_layers is None else n_layers
+    N, ppr = cfg.n_rollouts, cfg.pages_per_rollout
+    P = N * ppr + extra_pages
+    kv = randn_bf16((L, 2, P, cfg.page_tokens, cfg.n_kv_heads, cfg.head_dim), g, device)
+    perm = torch.randperm(P, generator=g, device=device)[:N * ppr]
+    block_table = perm.to(torch.int32).reshape(N, ppr).contiguous()
+    if ragged:
+        seq_len = torch.randint(1, cfg.ckpt_len + 1, (N,), generator=g, device=device, dtype=torch.int32)
+    else:
+        seq_len = torch.full((N,), cfg.ckpt_len, dtype=torch.int32, device=device)
+    tokens = torch.randint(0, cfg.vocab, (N, cfg.ckpt_len), generator=g, device=device, dtype=torch.int32)
+    return kv, block_table, seq_len, tokens
+
+
+def response_lengths(cfg, device="cpu"):
+    """Survivor response lengths, i.i.d. uniform integers in [resp_lo, resp_hi] (host tensor)."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(BASE_SEED + 1000 * cfg.index + 4)
+    return torch.randint(cfg.resp_lo, cfg.resp_hi + 1, (cfg.n_keep,), generator=g, dtype=torch.int64)
+
+
+def logprob_inputs(cfg, device, T=None, vocab=None):
+    """Packed survivor hidden states [T, d] bf16 ~ N(0,1), LM head [V, d] bf16 ~ N(0, 1/d),
+    targets uniform over the vocabulary, cu_seqlens of the ragged survivors."""
+    g = _gen(cfg, 5, device)
+    lens = response_lengths(cfg)
+    cu = torch.zeros(cfg.n_keep + 1, dtype=torch.int64)
+    cu[1:] = torch.cumsum(lens, 0)
+    total = int(cu[-1]) if T is None else T
+    V = cfg.vocab if vocab is None else vocab
+    lm_head = randn_bf16((V, cfg.d), g, device, std=cfg.d ** -0.5)
+    hidden = randn_bf16((total, cfg.d), g, device)
+    targets = torch.randint(0, V, (total,), generator=g, device=device, dtype=torch.int32)
+    return hidden, lm_head, targets, cu
+
+
+def vote_inputs(cfg, device):
+    """Candidate hidden states for the quality head and answer ids uniform in [0, A)."""
+    g = _gen(cfg, 6, device)
+    n = cfg.vote_q * cfg.vote_c
+    hidden = randn_bf16((n, cfg.d), g, device)
+    answer_id = torch.randint(0, cfg.vote_a, (n,), generator=g, device=device, dtype=torch.int32)
+    return hidden, answer_id

@@ -1,0 +1,23 @@
+"""Test-side glue: move torch tensors to the numpy forms the oracle takes."""
+import numpy as np
+import torch
+
+
+def bits(t):
+    """bf16 torch tensor (any device) -> uint16 numpy array of its bit patterns."""
+    assert t.dtype == torch.bfloat16
+    return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
+def npy(t):
+    return t.detach().cpu().numpy()
+
+
+def f32_to_bf16_bits(x):
+    """Round-to-nearest-even float32 -> bf16 bit patterns."""
+    u = np.asarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    return ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+
+
+def bf16_tensor_from_bits(b, device):
+    return torch.from_numpy(np.ascontiguousarray(b).view(np.int16)).view(torch.bfloat16).to(device)

@@ -1,0 +1,106 @@
+"""Host-side checks that need no GPU: the C-ABI library loads, exports every symbol the
+header declares, and rejects bad arguments before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "arrol.h")
+
+
+@pytest.fixture(scope="module")
+def pkg():
+    import paper_2603_24840_amd as A
+    if not os.path.exists(A.LIB_PATH):
+        from paper_2603_24840_amd import build
+        build.build(verbose=False)
+    return A
+
+
+def declared_functions():
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    return sorted(set(re.findall(r"\b(arrol_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_five_stage_calls():
+    names = declared_functions()
+    for fn in ["arrol_score", "arrol_select", "arrol_compact", "arrol_logprob", "arrol_weighted_vote",
+               "arrol_compact_workspace_bytes", "arrol_logprob_workspace_bytes", "arrol_version",
+               "arrol_error_string", "arrol_set_tuning"]:
+        assert fn in names
+
+
+def test_library_exports_every_declared_symbol(pkg):
+    handle = ctypes.CDLL(pkg.LIB_PATH)
+    for fn in declared_functions():
+        assert hasattr(handle, fn), fn
+
+
+def test_binding_covers_every_declared_symbol(pkg):
+    from paper_2603_24840_amd import binding
+    assert sorted(binding._SIGNATURES) == declared_functions()
+
+
+def test_version_and_error_strings(pkg):
+    assert pkg.version() >= 100
+    assert pkg.error_string(0) == "ok"
+    for code in (-1, -2, -3, -99):
+        assert pkg.error_string(code)
+
+
+def test_workspace_queries_are_pure_host_arithmetic(pkg):
+    assert pkg.arrol_compact_workspace_bytes(0) >= 4
+    assert pkg.arrol_compact_workspace_bytes(256) >= 257 * 4
+    assert pkg.arrol_logprob_workspace_bytes(0, 100, 64) == 0
+    small = pkg.arrol_logprob_workspace_bytes(2048, 4096, 256)
+    big = pkg.arrol_logprob_workspace_bytes(294912, 128256, 2048)
+    assert small >= 2048 * 12 and big >= 294912 * 12 and big % 256 == 0
+
+
+def test_bad_arguments_are_rejected_on_the_host(pkg):
+    L = pkg.lib()
+    fake = ctypes.c_void_p(0x1000)      # never dereferenced: validation fails first
+    # select: K > G, G > 64, K < 1, rho outside [0,1]
+    assert L.arrol_select(fake, 4, 8, 9, 0.5, fake, fake, None) == -1
+    assert L.arrol_select(fake, 4, 65, 4, 0.5, fake, fake, None) == -1
+    assert L.arrol_select(fake, 4, 8, 0, 0.5, fake, fake, None) == -1
+    assert L.arrol_select(fake, 4, 8, 4, 1.5, fake, fake, None) == -1
+    assert L.arrol_select(None, 4, 8, 4, 0.5, fake, fake, None) == -1
+    assert L.arrol_select(None, 0, 8, 4, 0.5, None, None, None) == 0        # empty batch is a no-op
+    # score: d not a multiple of 8, stride < d, misaligned base
+    assert L.arrol_score(fake, 12, None, fake, 0.0, 4, 12, None, fake, None) == -1
+    assert L.arrol_score(fake, 8, None, fake, 0.0, 4, 16, None, fake, None) == -1
+    assert L.arrol_score(ctypes.c_void_p(0x1004), 16, None, fake, 0.0, 4, 16, None, fake, None) == -1
+    assert L.arrol_score(None, 16, None, None, 0.0, 0, 16, None, None, None) == 0
+    # logprob: bad d, missing workspace
+    assert L.arrol_logprob(fake, fake, fake, 10, 100, 12, fake, None, fake, 1 << 20, None) == -1
+    assert L.arrol_logprob(fake, fake, fake, 10, 0, 16, fake, None, fake, 1 << 20, None) == -1
+    assert L.arrol_logprob(fake, fake, fake, 10, 100, 16, fake, None, None, 0, None) == -2
+    assert L.arrol_logprob(fake, fake, fake, 10, 100, 16, fake, None, fake, 8, None) == -2
+    assert L.arrol_logprob(None, None, None, 0, 100, 16, None, None, None, 0, None) == 0
+    # vote: C > 64, no answers
+    assert L.arrol_weighted_vote(fake, fake, 3, 65, 4, fake, None, None) == -1
+    assert L.arrol_weighted_vote(fake, fake, 3, 8, 0, fake, None, None) == -1
+    # compact: geometry mismatch, chunk not a multiple of 16 bytes, overlap, workspace
+    lay = pkg.KVLayout(2, 16, 2, 64, 128)
+    other = pkg.KVLayout(2, 16, 2, 32, 128)
+    odd = pkg.KVLayout(2, 1, 1, 4, 128)
+    far = ctypes.c_void_p(0x4000_0000)
+    args = (fake, fake, 4, None, 0, fake, 32, 16, fake, fake, None, fake, fake)
+    assert L.arrol_compact(fake, lay, far, other, *args, fake, 1 << 20, None) == -1
+    assert L.arrol_compact(fake, odd, far, odd, *args, fake, 1 << 20, None) == -1
+    assert L.arrol_compact(fake, lay, fake, lay, *args, fake, 1 << 20, None) == -1      # overlapping pools
+    assert L.arrol_compact(fake, lay, far, lay, *args, None, 0, None) == -2
+    assert L.arrol_compact(fake, lay, far, lay, *args, fake, 4, None) == -2
+    assert L.arrol_set_tuning(b"no_such_knob", 1) == -1
+
+
+def test_binding_refuses_cpu_tensors(pkg):
+    import torch
+    h = torch.zeros(4, 16, dtype=torch.bfloat16)
+    with pytest.raises((TypeError, ValueError)):
+        pkg.arrol_score(h, torch.zeros(16))
+    with pytest.raises(ValueError):
+        pkg.arrol_select(torch.zeros(8), 1, 8, 4)

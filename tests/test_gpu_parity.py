@@ -1,0 +1,313 @@
+"""Parity of the HIP library against the CPU oracle, element by element, through the C ABI.
+Bars: select / compact / vote bit-exact; probabilities within 1e-3; log-probs within 2e-3."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from helpers import bits, npy, bf16_tensor_from_bits, f32_to_bf16_bits
+
+pytestmark = pytest.mark.gpu
+
+PROB_TOL = 1e-3
+LOGP_TOL = 2e-3
+
+
+@pytest.fixture(scope="module")
+def A():
+    import paper_2603_24840_amd as pkg
+    pkg.lib()  # raises if libarrol.so is not built: no fallback
+    return pkg
+
+
+@pytest.fixture(scope="module")
+def W():
+    from paper_2603_24840_amd import workloads
+    return workloads
+
+
+DEV = "cuda:0"
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+
+
+# ------------------------------------------------------------------------------- score
+@pytest.mark.parametrize("n,d", [(32, 256), (1, 8), (5, 264), (1000, 2048), (257, 4096), (3, 16392)])
+def test_score_matches_oracle(A, n, d):
+    say("score n=%d d=%d" % (n, d))
+    g = torch.Generator(device=DEV); g.manual_seed(n * 7919 + d)
+    hidden = torch.randn(n, d, generator=g, device=DEV).to(torch.bfloat16)
+    w = torch.randn(d, generator=g, device=DEV) * d ** -0.5
+    s, q = A.arrol_score(hidden, w, bias=0.25)
+    torch.cuda.synchronize()
+    so, qo = O.score(bits(hidden), npy(w), 0.25)
+    assert np.max(np.abs(npy(s) - so)) < 1e-3
+    assert np.max(np.abs(npy(q) - qo)) < PROB_TOL
+
+
+def test_score_strided_rows_and_row_index(A):
+    say("score strided / gathered rows")
+    g = torch.Generator(device=DEV); g.manual_seed(5)
+    big = torch.randn(64, 512, generator=g, device=DEV).to(torch.bfloat16)
+    w = torch.randn(256, generator=g, device=DEV) / 16
+    view = big[:, 128:384]                      # row stride 512, offset 128 elements (256 bytes)
+    s, q = A.arrol_score(view, w)
+    idx = torch.tensor([63, 0, 7, 7, 31], dtype=torch.int64, device=DEV)
+    s2, q2 = A.arrol_score(view, w, row_index=idx)
+    torch.cuda.synchronize()
+    so, qo = O.score(bits(view.contiguous()), npy(w), 0.0)
+    assert np.max(np.abs(npy(q) - qo)) < PROB_TOL
+    assert np.max(np.abs(npy(q2) - qo[npy(idx)])) < PROB_TOL
+    assert np.max(np.abs(npy(s2) - so[npy(idx)])) < 1e-3
+
+
+def test_score_saturates_without_nan(A):
+    hidden = torch.zeros(4, 64, dtype=torch.bfloat16, device=DEV)
+    w = torch.zeros(64, device=DEV)
+    for b, expect in [(100.0, 1.0), (-100.0, 0.0), (0.0, 0.5), (-1000.0, 0.0), (1000.0, 1.0)]:
+        _, q = A.arrol_score(hidden, w, bias=b)
+        assert torch.all(torch.isfinite(q)) and abs(float(q[0]) - expect) < 1e-6
+
+
+# ------------------------------------------------------------------------------- select
+@pytest.mark.parametrize("n_groups,G,K", [(4, 8, 4), (1, 1, 1), (3, 2, 1), (64, 8, 4), (64, 16, 8),
+                                          (37, 64, 32), (5, 64, 1), (9, 13, 13), (130, 5, 2)])
+def test_select_bit_exact(A, n_groups, G, K):
+    say("select n_groups=%d G=%d K=%d" % (n_groups, G, K))
+    rng = np.random.default_rng(n_groups * 1000 + G * 10 + K)
+    for mode, rho in [("uniform", 0.5), ("grid", 0.5), ("skew", 0.3), ("const", 0.5), ("uniform", 1.0)]:
+        if mode == "uniform":
+            p = rng.random(n_groups * G)
+        elif mode == "grid":
+            p = rng.integers(0, 9, n_groups * G) / 8.0        # many exact ties
+        elif mode == "skew":
+            p = rng.beta(0.3, 2.0, n_groups * G)
+        else:
+            p = np.full(n_groups * G, 0.625)
+        p = p.astype(np.float32)
+        keep, surv = A.arrol_select(torch.from_numpy(p).to(DEV), n_groups, G, K, rho)
+        torch.cuda.synchronize()
+        keep_o, surv_o = O.select(p, n_groups, G, K, rho)
+        assert np.array_equal(npy(keep), keep_o), mode
+        assert np.array_equal(npy(surv), surv_o), mode
+
+
+def test_score_then_select_tiny_config(A, W):
+    cfg = W.CONFIGS["tiny"]
+    hidden, w, b = W.score_inputs(cfg, DEV)
+    _, q = A.arrol_score(hidden, w, b)
+    keep, surv = A.arrol_select(q, cfg.n_prompts, cfg.G, cfg.K, cfg.rho)
+    torch.cuda.synchronize()
+    _, qo = O.score(bits(hidden), npy(w), b)
+    assert np.max(np.abs(npy(q) - qo)) < PROB_TOL
+    # selection is compared when both sides are fed identical probabilities
+    keep_o, surv_o = O.select(npy(q), cfg.n_prompts, cfg.G, cfg.K, cfg.rho)
+    assert np.array_equal(npy(keep), keep_o) and np.array_equal(npy(surv), surv_o)
+    keep2, surv2 = A.arrol_select(torch.from_numpy(qo.astype(np.float32)).to(DEV), cfg.n_prompts, cfg.G, cfg.K, cfg.rho)
+    keep_o2, surv_o2 = O.select(qo.astype(np.float32), cfg.n_prompts, cfg.G, cfg.K, cfg.rho)
+    assert np.array_equal(npy(keep2), keep_o2) and np.array_equal(npy(surv2), surv_o2)
+
+
+# ------------------------------------------------------------------------------- compact
+def run_compact_case(A, kv, bt, sl, tok, surv, n_pages_dst, poison=0x7FC1):
+    dst = torch.full((kv.shape[0], 2, n_pages_dst) + tuple(kv.shape[3:]), 0, dtype=torch.int16, device=DEV)
+    dst.fill_(poison - 65536 if poison > 32767 else poison)
+    dst = dst.view(torch.bfloat16)
+    out = A.arrol_compact(kv, dst, bt, sl, tok, surv)
+    torch.cuda.synchronize()
+    ref = O.compact(bits(kv), npy(bt), npy(sl), npy(tok), npy(surv), n_pages_dst, fill=poison)
+    assert np.array_equal(bits(dst), ref["kv_dst"])
+    assert np.array_equal(npy(out["block_table_dst"]), ref["block_table_dst"])
+    assert np.array_equal(npy(out["seq_len_dst"]), ref["seq_len_dst"])
+    assert np.array_equal(npy(out["tokens_dst"]), ref["tokens_dst"])
+    assert np.array_equal(npy(out["src_of_dst"]), ref["src_of_dst"])
+    assert int(out["n_pages_used"][0]) == ref["n_pages_used"]
+    return out, ref
+
+
+def test_compact_tiny_config(A, W):
+    cfg = W.CONFIGS["tiny"]
+    say("compact tiny config")
+    kv, bt, sl, tok = W.compact_inputs(cfg, DEV)
+    p = W.select_inputs(cfg, DEV)
+    _, surv = A.arrol_select(p, cfg.n_prompts, cfg.G, cfg.K, cfg.rho)
+    run_compact_case(A, kv, bt, sl, tok, surv, cfg.n_keep * cfg.pages_per_rollout)
+
+
+@pytest.mark.parametrize("head_dim,pt,ragged,extra", [(64, 16, True, 5), (128, 16, True, 0), (8, 1, True, 3),
+                                                     (40, 3, False, 1)])
+def test_compact_ragged_and_odd_chunks(A, W, head_dim, pt, ragged, extra):
+    say("compact hd=%d page=%d ragged=%s" % (head_dim, pt, ragged))
+    cfg = W.shrink(W.CONFIGS["tiny"], n_prompts=6, G=5, K=2, head_dim=head_dim, page_tokens=pt, ckpt_len=37,
+                   n_layers=3, n_kv_heads=2)
+    kv, bt, sl, tok = W.compact_inputs(cfg, DEV, extra_pages=extra, ragged=ragged)
+    g = torch.Generator(device="cpu"); g.manual_seed(3)
+    pick = torch.stack([torch.sort(torch.randperm(cfg.G, generator=g)[:cfg.K])[0] + i * cfg.G
+                        for i in range(cfg.n_prompts)]).reshape(-1).to(torch.int32).to(DEV)
+    out, ref = run_compact_case(A, kv, bt, sl, tok, pick, cfg.n_keep * cfg.pages_per_rollout + 2)
+    if ragged:
+        assert ref["n_pages_used"] < cfg.n_keep * cfg.pages_per_rollout
+
+
+def test_compact_never_reads_pruned_pages_and_is_deterministic(A, W):
+    cfg = W.shrink(W.CONFIGS["tiny"], n_prompts=8)
+    kv, bt, sl, tok = W.compact_inputs(cfg, DEV, extra_pages=7)
+    surv = torch.arange(0, cfg.n_rollouts, 2, dtype=torch.int32, device=DEV)
+    n_dst = surv.numel() * cfg.pages_per_rollout
+    dst1 = torch.zeros((cfg.n_layers, 2, n_dst) + tuple(kv.shape[3:]), dtype=torch.bfloat16, device=DEV)
+    A.arrol_compact(kv, dst1, bt, sl, tok, surv)
+    live = bt[surv.long()].reshape(-1).long()
+    dead = torch.ones(kv.shape[2], dtype=torch.bool, device=DEV); dead[live] = False
+    kv2 = kv.clone(); kv2[:, :, dead] = float("nan")
+    for _ in range(3):
+        dst2 = torch.zeros_like(dst1)
+        A.arrol_compact(kv2, dst2, bt, sl, tok, surv)
+        torch.cuda.synchronize()
+        assert torch.equal(dst1.view(torch.int16), dst2.view(torch.int16))
+
+
+def test_compact_empty_and_identity(A, W):
+    cfg = W.CONFIGS["tiny"]
+    kv, bt, sl, tok = W.compact_inputs(cfg, DEV)
+    none = torch.empty(0, dtype=torch.int32, device=DEV)
+    dst = torch.zeros((cfg.n_layers, 2, 4) + tuple(kv.shape[3:]), dtype=torch.bfloat16, device=DEV)
+    out = A.arrol_compact(kv, dst, bt, sl, tok, none)
+    torch.cuda.synchronize()
+    assert int(out["n_pages_used"][0]) == 0 and not dst.view(torch.int16).any()
+    # K == G with a dense table is the identity
+    dense = torch.arange(cfg.n_rollouts * cfg.pages_per_rollout, dtype=torch.int32, device=DEV).reshape(cfg.n_rollouts, -1)
+    dst = torch.zeros_like(kv)
+    out = A.arrol_compact(kv, dst, dense, sl, tok, torch.arange(cfg.n_rollouts, dtype=torch.int32, device=DEV))
+    torch.cuda.synchronize()
+    assert torch.equal(dst.view(torch.int16), kv.view(torch.int16))
+    assert torch.equal(out["block_table_dst"], dense)
+
+
+def test_compact_out_of_range_indices_are_skipped(A, W):
+    # defensive behaviour stated in the header: no out-of-bounds access, bad ids are skipped
+    cfg = W.CONFIGS["tiny"]
+    kv, bt, sl, tok = W.compact_inputs(cfg, DEV)
+    bt = bt.clone(); bt[3, 1] = kv.shape[2] + 100; bt[3, 2] = -5
+    surv = torch.tensor([3, -1, 10_000, 4], dtype=torch.int32, device=DEV)
+    dst = torch.zeros((cfg.n_layers, 2, 16) + tuple(kv.shape[3:]), dtype=torch.bfloat16, device=DEV)
+    out = A.arrol_compact(kv, dst, bt, sl, tok, surv)
+    torch.cuda.synchronize()
+    assert npy(out["src_of_dst"]).tolist() == [3, -1, -1, 4]
+    assert npy(out["seq_len_dst"]).tolist() == [64, 0, 0, 64]
+    assert int(out["n_pages_used"][0]) == 8
+    assert not dst[:, :, 1:3].view(torch.int16).any()           # skipped source pages leave dst untouched
+    assert torch.equal(dst[:, :, 0].view(torch.int16), kv[:, :, bt[3, 0].long()].view(torch.int16))
+    assert torch.equal(dst[:, :, 4].view(torch.int16), kv[:, :, bt[4, 0].long()].view(torch.int16))
+
+
+# ------------------------------------------------------------------------------- logprob
+def check_logprob(A, hidden, lm_head, targets, tol=LOGP_TOL):
+    lp, lse = A.arrol_logprob(hidden, lm_head, targets, want_lse=True)
+    torch.cuda.synchronize()
+    lp_o, lse_o = O.logprob(bits(hidden), bits(lm_head), npy(targets))
+    err = np.max(np.abs(npy(lp).astype(np.float64) - lp_o))
+    err_lse = np.max(np.abs(npy(lse).astype(np.float64) - lse_o))
+    assert err < tol and err_lse < tol, (err, err_lse)
+    return err
+
+
+def test_logprob_tiny_config(A, W):
+    cfg = W.CONFIGS["tiny"]
+    say("logprob tiny config")
+    hidden, lm_head, targets, cu = W.logprob_inputs(cfg, DEV)
+    assert hidden.shape == (2048, 256) and lm_head.shape == (4096, 256)
+    check_logprob(A, hidden, lm_head, targets)
+
+
+@pytest.mark.parametrize("T,V,d", [(1, 1, 8), (300, 1000, 72), (257, 4097, 128), (33, 300, 200), (700, 2049, 320),
+                                   (512, 129, 64), (65, 7000, 1024)])
+def test_logprob_ragged_shapes(A, T, V, d):
+    say("logprob T=%d V=%d d=%d" % (T, V, d))
+    g = torch.Generator(device=DEV); g.manual_seed(T * 31 + V * 7 + d)
+    hidden = torch.randn(T, d, generator=g, device=DEV).to(torch.bfloat16)
+    lm_head = (torch.randn(V, d, generator=g, device=DEV) * (2.0 * d ** -0.5)).to(torch.bfloat16)
+    targets = torch.randint(0, V, (T,), generator=g, device=DEV, dtype=torch.int32)
+    targets[0] = 0; targets[-1] = V - 1
+    check_logprob(A, hidden, lm_head, targets)
+
+
+@pytest.mark.parametrize("splits", [1, 2, 3, 5, 16])
+def test_logprob_independent_of_vocab_splits(A, splits):
+    say("logprob forced splits=%d" % splits)
+    g = torch.Generator(device=DEV); g.manual_seed(99)
+    T, V, d = 600, 4500, 256
+    hidden = torch.randn(T, d, generator=g, device=DEV).to(torch.bfloat16)
+    lm_head = (torch.randn(V, d, generator=g, device=DEV) * 0.2).to(torch.bfloat16)
+    targets = torch.randint(0, V, (T,), generator=g, device=DEV, dtype=torch.int32)
+    try:
+        A.set_tuning("logprob_splits", splits)
+        check_logprob(A, hidden, lm_head, targets)
+    finally:
+        A.set_tuning("logprob_splits", 0)
+
+
+def test_logprob_extreme_logits_and_bad_target(A):
+    say("logprob extreme logits")
+    T, V, d = 40, 600, 64
+    h = np.zeros((T, d), np.float32); h[:, 0] = 64.0; h[:, 1] = 1.0
+    Wm = np.zeros((V, d), np.float32); Wm[5, 0] = 1.0; Wm[300, 0] = -1.0; Wm[:, 1] = 0.5
+    hidden = bf16_tensor_from_bits(f32_to_bf16_bits(h), DEV)
+    lm_head = bf16_tensor_from_bits(f32_to_bf16_bits(Wm), DEV)
+    targets = torch.full((T,), 5, dtype=torch.int32, device=DEV)
+    targets[1] = 300; targets[2] = 7; targets[3] = V; targets[4] = -1
+    lp = A.arrol_logprob(hidden, lm_head, targets)
+    torch.cuda.synchronize()
+    lp = npy(lp)
+    lp_o, _ = O.logprob(bits(hidden), bits(lm_head), np.clip(npy(targets), 0, V - 1))
+    ok = np.ones(T, bool); ok[3] = ok[4] = False
+    assert np.max(np.abs(lp[ok] - lp_o[ok])) < LOGP_TOL
+    assert abs(lp[0]) < 1e-6 and abs(lp[1] + 128.0) < LOGP_TOL and abs(lp[2] + 64.0) < LOGP_TOL
+    assert math.isnan(lp[3]) and math.isnan(lp[4])           # out-of-range targets are loud
+
+
+def test_logprob_zero_head_is_uniform(A):
+    T, V, d = 70, 777, 64
+    hidden = torch.randn(T, d, device=DEV).to(torch.bfloat16)
+    lm_head = torch.zeros(V, d, dtype=torch.bfloat16, device=DEV)
+    targets = torch.randint(0, V, (T,), device=DEV, dtype=torch.int32)
+    lp = A.arrol_logprob(hidden, lm_head, targets)
+    assert float((lp + math.log(V)).abs().max()) < 1e-5
+
+
+# ------------------------------------------------------------------------------- vote
+@pytest.mark.parametrize("Q,C,n_ans", [(1, 8, 4), (512, 64, 16), (7, 1, 3), (33, 17, 100), (5, 64, 200), (100, 32, 2)])
+def test_vote_bit_exact(A, Q, C, n_ans):
+    say("vote Q=%d C=%d A=%d" % (Q, C, n_ans))
+    rng = np.random.default_rng(Q * 100 + C)
+    for ties in (False, True):
+        p = (rng.integers(0, 5, Q * C) / 4.0 if ties else rng.random(Q * C)).astype(np.float32)
+        ans = rng.integers(0, n_ans, Q * C).astype(np.int32)
+        win, tally = A.arrol_weighted_vote(torch.from_numpy(p).to(DEV), torch.from_numpy(ans).to(DEV), Q, C, n_ans,
+                                           want_tally=True)
+        torch.cuda.synchronize()
+        win_o, tally_o = O.weighted_vote(p, ans, Q, C, n_ans)
+        assert np.array_equal(npy(win), win_o) and np.array_equal(npy(tally), tally_o)
+
+
+def test_score_then_vote_tiny_config(A, W):
+    cfg = W.CONFIGS["tiny"]
+    hidden, ans = W.vote_inputs(cfg, DEV)
+    _, w, b = W.score_inputs(cfg, DEV)
+    _, q = A.arrol_score(hidden, w, b)
+    win = A.arrol_weighted_vote(q, ans, cfg.vote_q, cfg.vote_c, cfg.vote_a)
+    torch.cuda.synchronize()
+    win_o, _ = O.weighted_vote(npy(q), npy(ans), cfg.vote_q, cfg.vote_c, cfg.vote_a)
+    assert np.array_equal(npy(win), win_o)
+
+
+def test_whole_path_is_deterministic(A, W):
+    cfg = W.CONFIGS["tiny"]
+    hidden, lm_head, targets, _ = W.logprob_inputs(cfg, DEV)
+    first = A.arrol_logprob(hidden, lm_head, targets).clone()
+    for _ in range(2):
+        again = A.arrol_logprob(hidden, lm_head, targets)
+        assert torch.equal(first, again)
