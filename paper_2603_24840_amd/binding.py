@@ -98,7 +98,8 @@ def _check(fn, rc):
         raise ArrolError(fn, rc)
 
 
-def arrol_score(hidden, w, bias=0.0, row_index=None, out_score=None, out_prob=None, stream=None):
+def arrol_score(hidden, w, bias=0.0, row_index=None, out_score=None, out_prob=None, want_score=True,
+                stream=None):
     """hidden bf16 [R, d] (rows may be strided), w fp32 [d] -> (score fp32 [n], prob fp32 [n])."""
     if hidden.dim() != 2 or hidden.dtype != torch.bfloat16 or not hidden.is_cuda:
         raise TypeError("hidden must be a 2-D bf16 GPU tensor")
@@ -107,7 +108,7 @@ def arrol_score(hidden, w, bias=0.0, row_index=None, out_score=None, out_prob=No
     d = hidden.shape[1]
     n = hidden.shape[0] if row_index is None else row_index.numel()
     dev = hidden.device
-    if out_score is None:
+    if out_score is None and want_score:
         out_score = torch.empty(n, dtype=torch.float32, device=dev)
     if out_prob is None:
         out_prob = torch.empty(n, dtype=torch.float32, device=dev)
