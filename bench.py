@@ -35,6 +35,7 @@ def parse():
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=8192)
     ap.add_argument("--calibrate-copy", action="store_true")
+    ap.add_argument("--tune", default="", help="comma list key=value passed to arrol_set_tuning (experiments)")
     ap.add_argument("--only", default="", help="comma list of stages to run (profiling aid); default all")
     return ap.parse_args()
 
@@ -126,6 +127,9 @@ def main():
     from paper_2603_24840_amd import workloads as W
 
     A.lib()
+    for kv in (x for x in args.tune.split(",") if x):
+        k, v = kv.split("=")
+        A.set_tuning(k, int(v))
     dev = "cuda:0"
     cfg = W.CONFIGS[args.workload]
     only = set(x for x in args.only.split(",") if x)

@@ -18,6 +18,8 @@
 // merges the splits.  Workgroup ids are mapped so that the workgroups resident on one XCD
 // (ids congruent mod 8) form a (few token blocks) x (all splits) patch and share their
 // H and W tiles through that XCD's L2.
+#include <type_traits>
+
 #include "common.h"
 
 namespace {
@@ -58,21 +60,133 @@ struct LogprobArgs {
     int64_t T;
     int V, d;
     int n_tb, n_sp, n_vt;
+    int probe;              // timing probes (bit 0: no vmcnt waits, 1: no loads, 2: no epilogue); 0 in production
 };
 
+// Per-lane online-softmax state: the lane owns token (wave token base + j*32 + lane%32), j < TN.
+template <int TN>
+struct LaneState {
+    float run_m[TN], run_s[TN], tgt_z[TN];
+    int tgt[TN];
+};
+
+// Folds one finished accumulator tile into the running (max, sumexp, target logit) and clears it.
+// acc[i][j][v] is the logit of vocab row vrow0 + i*32 + (v/4)*8 + lh*4 + v%4 for the lane's token of
+// block j (MFMA 32x32 result layout); WROWS = vocab rows per wave tile.
+template <int TM, int TN, int WROWS>
+__device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[TM][TN], LaneState<TN>& st, int vrow0, int V, int lh) {
+    if (vrow0 + WROWS > V) {  // tile hangs over the end of the vocabulary
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const bool dead = vrow0 + i * 32 + (v >> 2) * 8 + lh * 4 + (v & 3) >= V;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) acc[i][j][v] = dead ? -INFINITY : acc[i][j][v];
+            }
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int rel = st.tgt[j] - vrow0;
+        const bool mine = rel >= 0 && rel < WROWS && ((rel >> 2) & 1) == lh;
+        if (__any(mine)) {
+            const int code = mine ? ((rel >> 5) * 16 + ((rel & 31) >> 3) * 4 + (rel & 3)) : -1;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    if (code == i * 16 + v) st.tgt_z[j] = acc[i][j][v];
+        }
+        float mx = acc[0][j][0];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, acc[i][j][v]);
+        const float m_new = fmaxf(st.run_m[j], mx);
+        const float neg = -m_new * kLog2e;
+        float sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                sum += __builtin_amdgcn_exp2f(fmaf(acc[i][j][v], kLog2e, neg));
+                acc[i][j][v] = 0.f;
+            }
+        // difference first: exactly 0 when the maximum did not move (also for the -1e30 sentinel)
+        st.run_s[j] = st.run_s[j] * __builtin_amdgcn_exp2f((st.run_m[j] - m_new) * kLog2e) + sum;
+        st.run_m[j] = m_new;
+    }
+}
+
+// End of a workgroup's vocabulary range: merge the two lane halves (same token, different vocab
+// rows), then the WM waves that share a token range (through LDS, `red` = [WM][3][BN] floats, the
+// staging memory being idle by now), and write the (max, sumexp, target logit) partial of split sp.
+template <int TN, int WM, int WN, int BN, int NT>
+__device__ __forceinline__ void write_partials(LaneState<TN>& st, float* red, int wm, int wn, int l31, int lh,
+                                               int tid, int64_t tok0, int64_t T, int sp, float* part) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const float om = __shfl_xor(st.run_m[j], 32, ARROL_WAVE);
+        const float os = __shfl_xor(st.run_s[j], 32, ARROL_WAVE);
+        const float oz = __shfl_xor(st.tgt_z[j], 32, ARROL_WAVE);
+        const float m = fmaxf(st.run_m[j], om);
+        st.run_s[j] = st.run_s[j] * __builtin_amdgcn_exp2f((st.run_m[j] - m) * kLog2e) +
+                      os * __builtin_amdgcn_exp2f((om - m) * kLog2e);
+        st.run_m[j] = m;
+        st.tgt_z[j] += oz;
+    }
+    if (lh == 0) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = wn * (BN / WN) + j * 32 + l31;
+            red[(wm * 3 + 0) * BN + col] = st.run_m[j];
+            red[(wm * 3 + 1) * BN + col] = st.run_s[j];
+            red[(wm * 3 + 2) * BN + col] = st.tgt_z[j];
+        }
+    }
+    __syncthreads();
+    for (int col = tid; col < BN; col += NT) {
+        const int64_t t = tok0 + col;
+        if (t >= T) continue;
+        float m = red[col], s = red[BN + col], z = red[2 * BN + col];
+#pragma unroll
+        for (int w = 1; w < WM; ++w) {
+            const float om = red[(w * 3 + 0) * BN + col], os = red[(w * 3 + 1) * BN + col];
+            const float mm = fmaxf(m, om);
+            s = s * __builtin_amdgcn_exp2f((m - mm) * kLog2e) + os * __builtin_amdgcn_exp2f((om - mm) * kLog2e);
+            m = mm;
+            z += red[(w * 3 + 2) * BN + col];
+        }
+        float* p = part + static_cast<int64_t>(sp) * 3 * T + t;
+        p[0] = m;
+        p[T] = s;
+        p[2 * T] = z;
+    }
+}
+
+// workgroup id -> (token block, vocab split): ids congruent mod 8 land on the same XCD, so an XCD
+// works on token blocks xcd, xcd+8, ... and, for each, on all splits back to back.
+__device__ __forceinline__ bool map_workgroup(const LogprobArgs& a, int& tb, int& sp, int& vt_lo, int& vt_hi) {
+    const int bid = blockIdx.x;
+    const int xcd = bid % kXcds, idx = bid / kXcds;
+    sp = idx % a.n_sp;
+    tb = (idx / a.n_sp) * kXcds + xcd;
+    if (tb >= a.n_tb) return false;
+    vt_lo = static_cast<int>(static_cast<int64_t>(a.n_vt) * sp / a.n_sp);
+    vt_hi = static_cast<int>(static_cast<int64_t>(a.n_vt) * (sp + 1) / a.n_sp);
+    return true;
+}
+
+// ---------------------------------------------------------------------------------------------
+// General kernel (any d that is a multiple of 8): global -> registers -> LDS, two LDS stages.
+// ---------------------------------------------------------------------------------------------
 template <class C>
 __global__ __launch_bounds__(C::NT) void logprob_kernel(LogprobArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int BM = C::BM, BN = C::BN, BK = C::BK, TM = C::TM, TN = C::TN;
 
-    // ---- workgroup -> (token block, vocab split), XCD-aware ------------------------------
-    const int bid = blockIdx.x;
-    const int xcd = bid % kXcds, idx = bid / kXcds;
-    const int sp = idx % a.n_sp;
-    const int tb = (idx / a.n_sp) * kXcds + xcd;
-    if (tb >= a.n_tb) return;
-    const int vt_lo = static_cast<int>(static_cast<int64_t>(a.n_vt) * sp / a.n_sp);
-    const int vt_hi = static_cast<int>(static_cast<int64_t>(a.n_vt) * (sp + 1) / a.n_sp);
+    int tb, sp, vt_lo, vt_hi;
+    if (!map_workgroup(a, tb, sp, vt_lo, vt_hi)) return;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / C::WN, wn = wave % C::WN;
@@ -115,14 +229,12 @@ __global__ __launch_bounds__(C::NT) void logprob_kernel(LogprobArgs a) {
         for (int p = 0; p < C::PB; ++p) *reinterpret_cast<uint4*>(sb + p * C::ROWS_PER_PASS * 128) = stage[C::PA + p];
     };
 
-    // ---- per-lane softmax state: lane owns token wn*(BN/WN) + j*32 + l31 for j < TN --------
-    float run_m[TN], run_s[TN], tgt_z[TN];
-    int tgt[TN];
+    LaneState<TN> st;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-        run_m[j] = kNegBig; run_s[j] = 0.f; tgt_z[j] = 0.f;
+        st.run_m[j] = kNegBig; st.run_s[j] = 0.f; st.tgt_z[j] = 0.f;
         const int64_t t = tok0 + wn * (BN / C::WN) + j * 32 + l31;
-        tgt[j] = t < a.T ? a.targets[t] : -1;
+        st.tgt[j] = t < a.T ? a.targets[t] : -1;
     }
 
     f32x16 acc[TM][TN];
@@ -169,96 +281,217 @@ __global__ __launch_bounds__(C::NT) void logprob_kernel(LogprobArgs a) {
         __syncthreads();
 
         if (++kc == n_kc) {
-            // ---- tile epilogue: acc[i][j][v] is the logit of vocab row
-            //      vrow0 + i*32 + (v/4)*8 + lh*4 + v%4 for this lane's token of block j ----------
-            const int vrow0 = vt * BM + wm * (BM / C::WM);
-            if (vrow0 + BM / C::WM > a.V) {  // tile hangs over the end of the vocabulary
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const bool dead = vrow0 + i * 32 + (v >> 2) * 8 + lh * 4 + (v & 3) >= a.V;
-#pragma unroll
-                        for (int j = 0; j < TN; ++j) acc[i][j][v] = dead ? -INFINITY : acc[i][j][v];
-                    }
-            }
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int rel = tgt[j] - vrow0;
-                const bool mine = rel >= 0 && rel < BM / C::WM && ((rel >> 2) & 1) == lh;
-                if (__any(mine)) {
-                    const int code = mine ? ((rel >> 5) * 16 + ((rel & 31) >> 3) * 4 + (rel & 3)) : -1;
-#pragma unroll
-                    for (int i = 0; i < TM; ++i)
-#pragma unroll
-                        for (int v = 0; v < 16; ++v)
-                            if (code == i * 16 + v) tgt_z[j] = acc[i][j][v];
-                }
-                float mx = acc[0][j][0];
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) mx = fmaxf(mx, acc[i][j][v]);
-                const float m_new = fmaxf(run_m[j], mx);
-                const float neg = -m_new * kLog2e;
-                float sum = 0.f;
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        sum += __builtin_amdgcn_exp2f(fmaf(acc[i][j][v], kLog2e, neg));
-                        acc[i][j][v] = 0.f;
-                    }
-                // difference first: exactly 0 when the maximum did not move (also for the -1e30 sentinel)
-                run_s[j] = run_s[j] * __builtin_amdgcn_exp2f((run_m[j] - m_new) * kLog2e) + sum;
-                run_m[j] = m_new;
-            }
+            tile_epilogue<TM, TN, BM / C::WM>(acc, st, vt * BM + wm * (BM / C::WM), a.V, lh);
             kc = 0;
             ++vt;
         }
     }
+    write_partials<TN, C::WM, C::WN, BN, C::NT>(st, reinterpret_cast<float*>(lds), wm, wn, l31, lh, tid, tok0,
+                                                 a.T, sp, a.part);
+}
 
-    // ---- merge the two lane halves (same token, different vocab rows) -------------------------
+// ---------------------------------------------------------------------------------------------
+// Fast kernel (d a multiple of 64): global -> LDS directly (no staging registers), a ring of
+// RING K32 slots.  Loads are issued two slots at a time, i.e. as whole 128-byte lines of every
+// tile row, three slot-times ahead of their use.
+// ---------------------------------------------------------------------------------------------
+template <int BM_, int BN_, int WM_, int WN_>
+struct RingTile {
+    static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
+    static constexpr int NT = WM * WN * ARROL_WAVE;
+    static constexpr int NW = WM * WN;
+    static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+    static constexpr int RING = 5;
+    static constexpr int SLOT_BYTES = (BM + BN) * 64;      // 32 k-values (64 bytes) of every tile row
+    static constexpr int LDS_BYTES = RING * SLOT_BYTES;
+    static constexpr int GA = BM / 16 / NW;                 // 16-row load groups of the W tile per wave
+    static constexpr int GB = BN / 16 / NW;
+    static constexpr int LOADS_PER_PAIR = 2 * (GA + GB);    // load instructions a wave issues per slot pair
+    static_assert(BM % (16 * NW) == 0 && BN % (16 * NW) == 0, "whole 16-row load groups per wave");
+    static_assert(LOADS_PER_PAIR <= 15, "the vmcnt immediate used below");
+};
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {  // s_waitcnt vmcnt(N) only (gfx9 encoding), N <= 15
+    __builtin_amdgcn_s_waitcnt(0x0F70 | N);
+}
+
+template <class C>
+__global__ __launch_bounds__(C::NT) void logprob_ring_kernel(LogprobArgs a) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    constexpr int BM = C::BM, BN = C::BN, TM = C::TM, TN = C::TN, RING = C::RING;
+    typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+    int tb, sp, vt_lo, vt_hi;
+    if (!map_workgroup(a, tb, sp, vt_lo, vt_hi)) return;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / C::WN, wn = wave % C::WN;
+    const int l31 = lane & 31, lh = lane >> 5;
+    const int64_t tok0 = static_cast<int64_t>(tb) * BN;
+    const int n_k64 = a.d / 64;
+    const int n_pairs = (vt_hi - vt_lo) * n_k64;     // one pair = two K32 slots = one 128-byte line per row
+    const int n_chunks = 2 * n_pairs;
+
+    // ---- loader geometry: one instruction moves 16 rows x 64 bytes; lane -> (row lane/4, physical
+    //      16-byte position lane%4), which holds logical chunk (lane%4) ^ ((row/4)%4) -----------
+    const int ld_row = lane >> 2;
+    const int ld_k = ((lane & 3) ^ ((lane >> 4) & 3)) * 8;   // element offset inside the K32 half
+    const uint16_t* b_row[C::GB];   // start of this lane's H rows (fixed for the workgroup)
+    const uint16_t* a_cur[C::GA];   // this lane's W rows at the K position of the next pair to load
+#pragma unroll
+    for (int g = 0; g < C::GB; ++g) {
+        int64_t row = tok0 + (wave * C::GB + g) * 16 + ld_row;
+        row = row < a.T ? row : a.T - 1;
+        b_row[g] = a.H + row * a.d + ld_k;
+    }
+    auto point_at_tile = [&](int vt) {
+#pragma unroll
+        for (int g = 0; g < C::GA; ++g) {
+            int64_t row = static_cast<int64_t>(vt) * BM + (wave * C::GA + g) * 16 + ld_row;
+            row = row < a.V ? row : a.V - 1;
+            a_cur[g] = a.W + row * a.d + ld_k;
+        }
+    };
+    int ld_vt = vt_lo, ld_k64 = 0, ld_slot = 0;
+    point_at_tile(ld_vt);
+    const unsigned lds0 = static_cast<unsigned>(reinterpret_cast<size_t>((lds_ptr_t)lds));
+    // The q-th of the LOADS_PER_PAIR load instructions this wave contributes to a slot pair:
+    // q = 2*g + h for the W rows (g < GA), 2*GA + 2*g + h for the H rows; h picks the K32 half / slot.
+    // Written as asm so that the compiler keeps its own LDS wait counters exact; completion is
+    // tracked by hand with s_waitcnt vmcnt + the workgroup barrier.
+    auto issue_one = [&](int q) {
+        const bool is_b = q >= 2 * C::GA;
+        const int g = (is_b ? q - 2 * C::GA : q) >> 1, h = q & 1;
+        const int s_h = h == 0 ? ld_slot : (ld_slot + 1 == RING ? 0 : ld_slot + 1);
+        const int r0 = (wave * (is_b ? C::GB : C::GA) + g) * 16;
+        const unsigned dst = lds0 + s_h * C::SLOT_BYTES + (is_b ? BM * 64 : 0) + r0 * 64;
+        const uint16_t* src = (is_b ? b_row[g] + ld_k64 * 64 : a_cur[g]) + h * 32;
+        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(dst) : "memory");
+    };
+    auto advance_pair = [&]() {
+#pragma unroll
+        for (int g = 0; g < C::GA; ++g) a_cur[g] += 64;
+        if (++ld_k64 == n_k64) { ld_k64 = 0; ++ld_vt; point_at_tile(ld_vt); }
+        ld_slot = ld_slot + 2 >= RING ? ld_slot + 2 - RING : ld_slot + 2;
+    };
+    auto issue_pair = [&]() {
+#pragma unroll
+        for (int q = 0; q < C::LOADS_PER_PAIR; ++q) issue_one(q);
+        advance_pair();
+    };
+
+    LaneState<TN> st;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-        const float om = __shfl_xor(run_m[j], 32, ARROL_WAVE);
-        const float os = __shfl_xor(run_s[j], 32, ARROL_WAVE);
-        const float oz = __shfl_xor(tgt_z[j], 32, ARROL_WAVE);
-        const float m = fmaxf(run_m[j], om);
-        run_s[j] = run_s[j] * __builtin_amdgcn_exp2f((run_m[j] - m) * kLog2e) +
-                   os * __builtin_amdgcn_exp2f((om - m) * kLog2e);
-        run_m[j] = m;
-        tgt_z[j] += oz;
+        st.run_m[j] = kNegBig; st.run_s[j] = 0.f; st.tgt_z[j] = 0.f;
+        const int64_t t = tok0 + wn * (BN / C::WN) + j * 32 + l31;
+        st.tgt[j] = t < a.T ? a.targets[t] : -1;
     }
-    // ---- merge the WM waves that share a token range, through LDS ---------------------------
-    float* red = reinterpret_cast<float*>(lds);  // [WM][3][BN]; the staging buffers are idle now
-    if (lh == 0) {
+    f32x16 acc[TM][TN];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = wn * (BN / C::WN) + j * 32 + l31;
-            red[(wm * 3 + 0) * BN + col] = run_m[j];
-            red[(wm * 3 + 1) * BN + col] = run_s[j];
-            red[(wm * 3 + 2) * BN + col] = tgt_z[j];
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    // fragment reads: row (wave base + i*32 + l31) of a slot, 16-byte chunk kk*2 + lh, swizzled
+    const int swz = (l31 >> 2) & 3;
+    const int a_off0 = (wm * (BM / C::WM) + l31) * 64 + ((lh ^ swz) << 4);          // K16 step 0
+    const int a_off1 = (wm * (BM / C::WM) + l31) * 64 + (((2 + lh) ^ swz) << 4);    // K16 step 1
+    const int b_off0 = BM * 64 + (wn * (BN / C::WN) + l31) * 64 + ((lh ^ swz) << 4);
+    const int b_off1 = BM * 64 + (wn * (BN / C::WN) + l31) * 64 + (((2 + lh) ^ swz) << 4);
+    bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];   // fragments of K16 step 0 / step 1
+    auto read_step0 = [&](const unsigned char* base) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb0[j] = *reinterpret_cast<const bf16x8*>(base + b_off0 + j * 32 * 64);
+#pragma unroll
+        for (int m = 0; m < TM; ++m) fa0[m] = *reinterpret_cast<const bf16x8*>(base + a_off0 + m * 32 * 64);
+    };
+
+    // Pipeline.  Chunk c lives in ring slot c % RING.  Pair p = chunks (2p, 2p+1) is requested during
+    // the odd iteration 2p-3 (pairs 0 and 1 up front), its loads interleaved with that iteration's
+    // MFMAs.  The barrier that opens iteration i certifies chunk i+1 (every wave has waited for its own
+    // part), because step 0 of chunk i+1 is read into registers during iteration i, so that the MFMAs
+    // after the next barrier start without an LDS round trip.
+    if (n_pairs > 0) issue_pair();
+    if (n_pairs > 1) issue_pair();
+    int issued = n_pairs < 2 ? n_pairs : 2;
+    if (n_pairs > 0) {
+        if (issued > 1) wait_vmcnt<C::LOADS_PER_PAIR>(); else wait_vmcnt<0>();
+        __syncthreads();
+        read_step0(lds);
+    }
+    int vt = vt_lo, kc = 0, slot = 0;
+    const int n_kc = 2 * n_k64;
+    constexpr int NMMA = TM * TN;                         // MFMAs per K16 step
+    constexpr int EVERY = 2 * NMMA / C::LOADS_PER_PAIR;    // one load after every EVERY-th MFMA
+    static_assert(EVERY >= 1 && 2 * NMMA % C::LOADS_PER_PAIR == 0, "loads spread evenly over the MFMAs");
+    // One K32 chunk: 2 x NMMA MFMAs.  Everything else is threaded between the MFMAs so that the matrix
+    // pipe always has the next instruction waiting: after every 2nd MFMA of K16 step 0 two fragment reads
+    // of this slot's step 1, after every 2nd MFMA of step 1 two reads of the NEXT slot's step 0 (after the
+    // last chunk that is a stale slot; never used), and, when `loads` (wave-uniform) is set, one of this
+    // wave's LOADS_PER_PAIR global->LDS loads of the next slot pair after every EVERY-th MFMA.
+    static_assert(TM + TN <= NMMA && NMMA % 2 == 0, "fragment reads fit between the MFMAs of one step");
+    auto read_frag = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], const unsigned char* base, int a_off, int b_off, int r) {
+        if (r < TN) fb[r] = *reinterpret_cast<const bf16x8*>(base + b_off + r * 32 * 64);
+        else if (r < TN + TM) fa[r - TN] = *reinterpret_cast<const bf16x8*>(base + a_off + (r - TN) * 32 * 64);
+    };
+    auto iteration = [&](bool loads) {
+        // this wave's LDS reads are complete before it tells the others that their slots may be refilled
+        __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0) only
+        __syncthreads();
+        const unsigned char* base = lds + slot * C::SLOT_BYTES;
+        slot = slot + 1 == RING ? 0 : slot + 1;
+        const unsigned char* next = lds + slot * C::SLOT_BYTES;
+#pragma unroll
+        for (int x = 0; x < NMMA; ++x) {
+            acc[x / TN][x % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[x / TN], fb0[x % TN], acc[x / TN][x % TN], 0, 0, 0);
+            if (x & 1) {
+                __builtin_amdgcn_sched_barrier(0);
+                read_frag(fa1, fb1, base, a_off1, b_off1, x - 1);
+                read_frag(fa1, fb1, base, a_off1, b_off1, x);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if ((x + 1) % EVERY == 0 && loads) issue_one((x + 1) / EVERY - 1);
+        }
+#pragma unroll
+        for (int x = 0; x < NMMA; ++x) {
+            acc[x / TN][x % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[x / TN], fb1[x % TN], acc[x / TN][x % TN], 0, 0, 0);
+            if (x & 1) {
+                __builtin_amdgcn_sched_barrier(0);
+                read_frag(fa0, fb0, next, a_off0, b_off0, x - 1);
+                read_frag(fa0, fb0, next, a_off0, b_off0, x);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if ((x + 1) % EVERY == 0 && loads) issue_one(NMMA / EVERY + (x + 1) / EVERY - 1);
+        }
+        if (loads) advance_pair();
+    };
+    for (int i = 0; i < n_chunks; i += 2) {
+        // even iteration: chunk i+1 belongs to the pair of chunk i (already certified); the pair requested
+        // during iteration i-1 may stay in flight
+        if (a.probe & 1) {} else if ((i >> 1) + 1 < issued) wait_vmcnt<C::LOADS_PER_PAIR>(); else wait_vmcnt<0>();
+        iteration(false);
+        // odd iteration: chunk i+2 opens the next pair: everything requested so far must have landed;
+        // slots i-1 and i (= i+4, i+5 mod RING) are free after its barrier and take the next pair
+        if (!(a.probe & 1)) wait_vmcnt<0>();
+        const bool loads = issued < n_pairs && !(a.probe & 2);
+        iteration(loads);
+        issued += loads ? 1 : 0;
+        kc += 2;
+        if (kc == n_kc) {   // a tile ends on an odd chunk (d is a multiple of 64)
+            if (!(a.probe & 4)) tile_epilogue<TM, TN, BM / C::WM>(acc, st, vt * BM + wm * (BM / C::WM), a.V, lh);
+            kc = 0;
+            ++vt;
         }
     }
-    __syncthreads();
-    for (int col = tid; col < BN; col += C::NT) {
-        const int64_t t = tok0 + col;
-        if (t >= a.T) continue;
-        float m = red[col], s = red[BN + col], z = red[2 * BN + col];
-#pragma unroll
-        for (int w = 1; w < C::WM; ++w) {
-            const float om = red[(w * 3 + 0) * BN + col], os = red[(w * 3 + 1) * BN + col];
-            const float mm = fmaxf(m, om);
-            s = s * __builtin_amdgcn_exp2f((m - mm) * kLog2e) + os * __builtin_amdgcn_exp2f((om - mm) * kLog2e);
-            m = mm;
-            z += red[(w * 3 + 2) * BN + col];
-        }
-        float* p = a.part + static_cast<int64_t>(sp) * 3 * a.T + t;
-        p[0] = m;
-        p[a.T] = s;
-        p[2 * a.T] = z;
-    }
+    wait_vmcnt<0>();
+    __syncthreads();   // every fragment read and every load into LDS has finished
+    write_partials<TN, C::WM, C::WN, BN, C::NT>(st, reinterpret_cast<float*>(lds), wm, wn, l31, lh, tid, tok0,
+                                                 a.T, sp, a.part);
 }
 
 __global__ __launch_bounds__(256) void logprob_finalize_kernel(
@@ -282,8 +515,12 @@ __global__ __launch_bounds__(256) void logprob_finalize_kernel(
 }
 
 using MainTile = Tile<256, 256, 64, 2, 4>;
+using FastTile = RingTile<256, 256, 2, 4>;
+static_assert(MainTile::BM == FastTile::BM && MainTile::BN == FastTile::BN, "one plan serves both kernels");
 
 int g_force_splits = 0;  // 0 = heuristic
+int g_force_general = 0; // 1 = use the general kernel even when d % 64 == 0
+int g_probe = 0;
 
 struct Plan { int n_tb, n_vt, n_sp; };
 
@@ -309,6 +546,8 @@ Plan make_plan(int64_t T, int V) {
 extern "C" int arrol_set_tuning(const char* key, int value) {
     if (!key) return ARROL_EINVAL;
     if (!__builtin_strcmp(key, "logprob_splits")) { g_force_splits = value; return ARROL_OK; }
+    if (!__builtin_strcmp(key, "logprob_general_kernel")) { g_force_general = value; return ARROL_OK; }
+    if (!__builtin_strcmp(key, "logprob_probe")) { g_probe = value; return ARROL_OK; }
     return ARROL_EINVAL;
 }
 
@@ -334,7 +573,9 @@ extern "C" int arrol_logprob(const void* hidden, const void* lm_head, const int3
     static bool attr_done = false;
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(&logprob_kernel<MainTile>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, MainTile::LDS_BYTES) != hipSuccess)
+                                hipFuncAttributeMaxDynamicSharedMemorySize, MainTile::LDS_BYTES) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void*>(&logprob_ring_kernel<FastTile>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, FastTile::LDS_BYTES) != hipSuccess)
             return ARROL_EHIP;
         attr_done = true;
     }
@@ -345,8 +586,12 @@ extern "C" int arrol_logprob(const void* hidden, const void* lm_head, const int3
     a.part = static_cast<float*>(workspace);
     a.T = T; a.V = V; a.d = d;
     a.n_tb = p.n_tb; a.n_sp = p.n_sp; a.n_vt = p.n_vt;
+    a.probe = g_probe;
     const int tb_pad = (p.n_tb + kXcds - 1) / kXcds * kXcds;
-    hipLaunchKernelGGL(logprob_kernel<MainTile>, dim3(tb_pad * p.n_sp), dim3(MainTile::NT), MainTile::LDS_BYTES, st, a);
+    if (d % 64 == 0 && !g_force_general)
+        hipLaunchKernelGGL(logprob_ring_kernel<FastTile>, dim3(tb_pad * p.n_sp), dim3(FastTile::NT), FastTile::LDS_BYTES, st, a);
+    else
+        hipLaunchKernelGGL(logprob_kernel<MainTile>, dim3(tb_pad * p.n_sp), dim3(MainTile::NT), MainTile::LDS_BYTES, st, a);
     if (hipGetLastError() != hipSuccess) return ARROL_EHIP;
     hipLaunchKernelGGL(logprob_finalize_kernel, dim3(static_cast<unsigned>((T + 255) / 256)), dim3(256), 0, st,
                        static_cast<const float*>(workspace), targets, T, V, p.n_sp, logprob_out, lse_out);
