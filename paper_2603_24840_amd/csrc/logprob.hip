@@ -442,7 +442,7 @@ __global__ __launch_bounds__(C::NT) void logprob_ring_kernel(LogprobArgs a) {
     auto iteration = [&](bool loads) {
         // this wave's LDS reads are complete before it tells the others that their slots may be refilled
         __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0) only
-        __syncthreads();
+        if (!(a.probe & 8)) __syncthreads();
         const unsigned char* base = lds + slot * C::SLOT_BYTES;
         slot = slot + 1 == RING ? 0 : slot + 1;
         const unsigned char* next = lds + slot * C::SLOT_BYTES;

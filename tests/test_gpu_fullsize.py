@@ -1,0 +1,157 @@
+"""Parity at the benchmark's full size (LLaMA-3.2-1B-shaped batch, same launch configuration
+bench.py times) on sampled outputs the oracle computes one by one, plus reduced-batch cases
+with the other configurations' geometry (d, vocab size, head_dim, group size)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from helpers import bits, npy
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def A():
+    import paper_2603_24840_amd as pkg
+    pkg.lib()
+    return pkg
+
+
+@pytest.fixture(scope="module")
+def W():
+    from paper_2603_24840_amd import workloads
+    return workloads
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+
+
+def sample_rows(T, n, V, targets, seed=7):
+    """Seeded row sample that always holds the first / last rows and rows whose target sits on a
+    vocabulary-tile edge or at the ends of the vocabulary."""
+    g = torch.Generator(device="cpu"); g.manual_seed(seed)
+    rows = set(torch.randperm(T, generator=g)[:n].tolist())
+    rows.update([0, 1, T - 1, T - 2, min(T - 1, 255), min(T - 1, 256)])
+    t = npy(targets)
+    for want in (0, V - 1, 255, 256, (V // 256) * 256 - 1, (V // 256) * 256 % V):
+        hit = np.flatnonzero(t == want)
+        if hit.size:
+            rows.add(int(hit[0]))
+    return torch.tensor(sorted(rows), dtype=torch.int64)
+
+
+def test_llama1b_prune_path_full_size(A, W):
+    cfg = W.CONFIGS["llama1b"]
+    say("llama1b score/select/vote, full batch")
+    hidden, w, b = W.score_inputs(cfg, DEV)
+    s, q = A.arrol_score(hidden, w, b)
+    keep, surv = A.arrol_select(q, cfg.n_prompts, cfg.G, cfg.K, cfg.rho)
+    _, ans = W.vote_inputs(cfg, DEV)
+    win, tally = A.arrol_weighted_vote(q, ans, cfg.vote_q, cfg.vote_c, cfg.vote_a, want_tally=True)
+    torch.cuda.synchronize()
+    so, qo = O.score(bits(hidden), npy(w), b)
+    assert np.max(np.abs(npy(q) - qo)) < 1e-3 and np.max(np.abs(npy(s) - so)) < 1e-3
+    keep_o, surv_o = O.select(npy(q), cfg.n_prompts, cfg.G, cfg.K, cfg.rho)
+    assert np.array_equal(npy(keep), keep_o) and np.array_equal(npy(surv), surv_o)
+    win_o, tally_o = O.weighted_vote(npy(q), npy(ans), cfg.vote_q, cfg.vote_c, cfg.vote_a)
+    assert np.array_equal(npy(win), win_o) and np.array_equal(npy(tally), tally_o)
+
+
+def test_llama1b_compact_full_size(A, W):
+    cfg = W.CONFIGS["llama1b"]
+    say("llama1b compact, full pool (8.6 GB), oracle on 4 of 16 layers + gather property on all")
+    kv, bt, sl, tok = W.compact_inputs(cfg, DEV)
+    p = W.select_inputs(cfg, DEV)
+    _, surv = A.arrol_select(p, cfg.n_prompts, cfg.G, cfg.K, cfg.rho)
+    n_dst = cfg.n_keep * cfg.pages_per_rollout
+    dst = torch.empty((cfg.n_layers, 2, n_dst) + tuple(kv.shape[3:]), dtype=torch.bfloat16, device=DEV)
+    dst.view(torch.int16).fill_(0x7FC1)
+    out = A.arrol_compact(kv, dst, bt, sl, tok, surv)
+    torch.cuda.synchronize()
+    surv_h, bt_h, sl_h, tok_h = npy(surv), npy(bt), npy(sl), npy(tok)
+    for layer in (0, 5, 10, cfg.n_layers - 1):
+        ref = O.compact(bits(kv[layer:layer + 1]), bt_h, sl_h, tok_h, surv_h, n_dst, fill=0x7FC1)
+        assert np.array_equal(bits(dst[layer:layer + 1]), ref["kv_dst"]), layer
+    assert np.array_equal(npy(out["block_table_dst"]), ref["block_table_dst"])
+    assert np.array_equal(npy(out["tokens_dst"]), ref["tokens_dst"])
+    assert np.array_equal(npy(out["seq_len_dst"]), ref["seq_len_dst"])
+    assert np.array_equal(npy(out["src_of_dst"]), ref["src_of_dst"])
+    assert int(out["n_pages_used"][0]) == ref["n_pages_used"] == n_dst
+    # every layer: destination page j holds source page flat[j]  (holds at any size)
+    flat = bt[surv.long()].reshape(-1).long()
+    for layer in range(cfg.n_layers):
+        for c in range(2):
+            assert torch.equal(dst[layer, c].view(torch.int16), kv[layer, c, flat].view(torch.int16)), (layer, c)
+
+
+def test_llama1b_logprob_full_size_sampled_rows(A, W):
+    cfg = W.CONFIGS["llama1b"]
+    say("llama1b logprob, full T x V x d, 160 sampled rows against the oracle")
+    hidden, lm_head, targets, cu = W.logprob_inputs(cfg, DEV)
+    T = hidden.shape[0]
+    assert 256 * cfg.n_keep <= T <= 2048 * cfg.n_keep and lm_head.shape == (128256, 2048)
+    lp, lse = A.arrol_logprob(hidden, lm_head, targets, want_lse=True)
+    torch.cuda.synchronize()
+    rows = sample_rows(T, 150, cfg.vocab, targets)
+    lp_o, lse_o = O.logprob(bits(hidden[rows.to(DEV)]), bits(lm_head), npy(targets)[rows.numpy()])
+    assert np.max(np.abs(npy(lp)[rows.numpy()] - lp_o)) < 2e-3
+    assert np.max(np.abs(npy(lse)[rows.numpy()] - lse_o)) < 2e-3
+    # whole output: finite, negative, and distributed as logits ~ N(0,1) imply (lse ~ log V + 1/2)
+    assert bool(torch.isfinite(lp).all()) and float(lp.max()) <= 0.0
+    assert abs(float(lse.mean()) - (np.log(cfg.vocab) + 0.5)) < 0.05
+
+
+@pytest.mark.parametrize("name,T", [("qwen1p7b", 300), ("llama3b", 257), ("qwen8b", 200)])
+def test_logprob_other_model_geometries(A, W, name, T):
+    cfg = W.CONFIGS[name]
+    say("logprob %s geometry: V=%d d=%d, T=%d" % (name, cfg.vocab, cfg.d, T))
+    hidden, lm_head, targets, _ = W.logprob_inputs(cfg, DEV, T=T)
+    targets[0] = cfg.vocab - 1; targets[1] = 0; targets[2] = (cfg.vocab // 256) * 256 - 1
+    lp = A.arrol_logprob(hidden, lm_head, targets)
+    torch.cuda.synchronize()
+    rows = sample_rows(T, 40, cfg.vocab, targets)
+    lp_o, _ = O.logprob(bits(hidden[rows.to(DEV)]), bits(lm_head), npy(targets)[rows.numpy()])
+    assert np.max(np.abs(npy(lp)[rows.numpy()] - lp_o)) < 2e-3
+    assert bool(torch.isfinite(lp).all())
+
+
+@pytest.mark.parametrize("name", ["qwen1p7b", "llama3b", "qwen8b"])
+def test_prune_path_other_model_geometries(A, W, name):
+    full = W.CONFIGS[name]
+    cfg = W.shrink(full, n_prompts=6, n_layers=3)          # same d, G, K, head_dim, page size, checkpoint length
+    say("prune path %s geometry: G=%d K=%d d=%d hd=%d, %d prompts, %d layers"
+        % (name, cfg.G, cfg.K, cfg.d, cfg.head_dim, cfg.n_prompts, cfg.n_layers))
+    hidden, w, b = W.score_inputs(cfg, DEV)
+    kv, bt, sl, tok = W.compact_inputs(cfg, DEV, extra_pages=9)
+    _, q = A.arrol_score(hidden, w, b)
+    keep, surv = A.arrol_select(q, cfg.n_prompts, cfg.G, cfg.K, cfg.rho)
+    n_dst = cfg.n_keep * cfg.pages_per_rollout
+    dst = torch.zeros((cfg.n_layers, 2, n_dst) + tuple(kv.shape[3:]), dtype=torch.bfloat16, device=DEV)
+    out = A.arrol_compact(kv, dst, bt, sl, tok, surv)
+    torch.cuda.synchronize()
+    _, qo = O.score(bits(hidden), npy(w), b)
+    assert np.max(np.abs(npy(q) - qo)) < 1e-3
+    keep_o, surv_o = O.select(npy(q), cfg.n_prompts, cfg.G, cfg.K, cfg.rho)
+    assert np.array_equal(npy(keep), keep_o) and np.array_equal(npy(surv), surv_o)
+    ref = O.compact(bits(kv), npy(bt), npy(sl), npy(tok), surv_o, n_dst)
+    assert np.array_equal(bits(dst), ref["kv_dst"])
+    assert np.array_equal(npy(out["block_table_dst"]), ref["block_table_dst"])
+    assert np.array_equal(npy(out["tokens_dst"]), ref["tokens_dst"])
+
+
+def test_vote_test_time_shape_qwen8b(A, W):
+    cfg = W.CONFIGS["qwen8b"]
+    say("test-time scaling shape: %d questions x %d candidates, d=%d" % (cfg.vote_q, cfg.vote_c, cfg.d))
+    hidden, ans = W.vote_inputs(cfg, DEV)
+    _, w, b = W.score_inputs(cfg, DEV, n_rows=1)
+    _, q = A.arrol_score(hidden, w, b)
+    win, tally = A.arrol_weighted_vote(q, ans, cfg.vote_q, cfg.vote_c, cfg.vote_a, want_tally=True)
+    torch.cuda.synchronize()
+    rows = np.arange(0, hidden.shape[0], 97)
+    _, qo = O.score(bits(hidden[torch.from_numpy(rows).to(DEV)]), npy(w), b)
+    assert np.max(np.abs(npy(q)[rows] - qo)) < 1e-3
+    win_o, tally_o = O.weighted_vote(npy(q), npy(ans), cfg.vote_q, cfg.vote_c, cfg.vote_a)
+    assert np.array_equal(npy(win), win_o) and np.array_equal(npy(tally), tally_o)
