@@ -5,16 +5,16 @@
 // Two launches on the caller's stream, no host round trip:
 //   plan  one workgroup: pages per survivor, exclusive prefix scan (wave scan + LDS carry),
 //         destination block tables / lengths / source map / page count.
-//   copy  HBM streaming: one workgroup per (layer, K|V, survivor, logical page) chunk, every
-//         lane moving 16 bytes per access with all loads of a chunk issued before its stores;
-//         extra workgroups move the token rows.
+//   copy  HBM streaming: one 512-lane workgroup per (layer, K|V, survivor, logical page) chunk,
+//         every lane moving 16 bytes per access (non-temporal), the loads of a 16 KiB pass issued
+//         before its stores; extra workgroups move the token rows.
 #include "common.h"
 
 namespace {
 
 constexpr int kPlanThreads = 1024;
-constexpr int kCopyThreads = 256;
-constexpr int kCopyUnroll = 8;  // 16-byte accesses in flight per lane
+constexpr int kCopyThreads = 512;  // measured: 512 lanes x 2 accesses per 16 KiB chunk streams fastest
+constexpr int kCopyUnroll = 2;     // 16-byte accesses per lane issued before the stores
 
 __device__ __forceinline__ int pages_of(const int32_t* seq_len_src, int src, int n_src, int page_tokens, int ppr) {
     if (src < 0 || src >= n_src) return 0;

@@ -60,7 +60,6 @@ struct LogprobArgs {
     int64_t T;
     int V, d;
     int n_tb, n_sp, n_vt;
-    int probe;              // timing probes (bit 0: no vmcnt waits, 1: no loads, 2: no epilogue); 0 in production
 };
 
 // Per-lane online-softmax state: the lane owns token (wave token base + j*32 + lane%32), j < TN.
@@ -337,26 +336,38 @@ __global__ __launch_bounds__(C::NT) void logprob_ring_kernel(LogprobArgs a) {
     // ---- loader geometry: one instruction moves 16 rows x 64 bytes; lane -> (row lane/4, physical
     //      16-byte position lane%4), which holds logical chunk (lane%4) ^ ((row/4)%4) -----------
     const int ld_row = lane >> 2;
-    const int ld_k = ((lane & 3) ^ ((lane >> 4) & 3)) * 8;   // element offset inside the K32 half
-    const uint16_t* b_row[C::GB];   // start of this lane's H rows (fixed for the workgroup)
-    const uint16_t* a_cur[C::GA];   // this lane's W rows at the K position of the next pair to load
+    const int ld_kb = ((lane & 3) ^ ((lane >> 4) & 3)) * 16;   // byte offset inside the K32 half
+    // Addresses are (wave-uniform 64-bit base in SGPRs) + (per-lane 32-bit byte offset): the base
+    // carries tile and K position, the lane offset the row inside the tile (clamped at the end of the
+    // vocabulary / token range, so every load stays inside W and H) and the swizzled chunk.
+    const int64_t row_bytes = static_cast<int64_t>(a.d) * 2;
+    unsigned a_voff[C::GA], b_voff[C::GB];
+    {
+        const int64_t rows_valid = a.T - tok0 < BN ? a.T - tok0 : BN;
 #pragma unroll
-    for (int g = 0; g < C::GB; ++g) {
-        int64_t row = tok0 + (wave * C::GB + g) * 16 + ld_row;
-        row = row < a.T ? row : a.T - 1;
-        b_row[g] = a.H + row * a.d + ld_k;
+        for (int g = 0; g < C::GB; ++g) {
+            int64_t r = (wave * C::GB + g) * 16 + ld_row;
+            r = r < rows_valid ? r : rows_valid - 1;
+            b_voff[g] = static_cast<unsigned>(r * row_bytes + ld_kb);
+        }
     }
     auto point_at_tile = [&](int vt) {
+        const int64_t left = static_cast<int64_t>(a.V) - static_cast<int64_t>(vt) * BM;
+        const int64_t rows_valid = left < BM ? (left > 0 ? left : 1) : BM;   // left <= 0 only past the last pair
 #pragma unroll
         for (int g = 0; g < C::GA; ++g) {
-            int64_t row = static_cast<int64_t>(vt) * BM + (wave * C::GA + g) * 16 + ld_row;
-            row = row < a.V ? row : a.V - 1;
-            a_cur[g] = a.W + row * a.d + ld_k;
+            int64_t r = (wave * C::GA + g) * 16 + ld_row;
+            r = r < rows_valid ? r : rows_valid - 1;
+            a_voff[g] = static_cast<unsigned>(r * row_bytes + ld_kb);
         }
     };
     int ld_vt = vt_lo, ld_k64 = 0, ld_slot = 0;
     point_at_tile(ld_vt);
     const unsigned lds0 = static_cast<unsigned>(reinterpret_cast<size_t>((lds_ptr_t)lds));
+    // uniform bases of the next pair to load: W tile ld_vt / H token block, at K position ld_k64*64
+    const int64_t tile_bytes = BM * row_bytes;
+    const char* a_base = reinterpret_cast<const char*>(a.W) + ld_vt * tile_bytes;
+    const char* b_base = reinterpret_cast<const char*>(a.H) + tok0 * row_bytes;
     // The q-th of the LOADS_PER_PAIR load instructions this wave contributes to a slot pair:
     // q = 2*g + h for the W rows (g < GA), 2*GA + 2*g + h for the H rows; h picks the K32 half / slot.
     // Written as asm so that the compiler keeps its own LDS wait counters exact; completion is
@@ -367,13 +378,20 @@ __global__ __launch_bounds__(C::NT) void logprob_ring_kernel(LogprobArgs a) {
         const int s_h = h == 0 ? ld_slot : (ld_slot + 1 == RING ? 0 : ld_slot + 1);
         const int r0 = (wave * (is_b ? C::GB : C::GA) + g) * 16;
         const unsigned dst = lds0 + s_h * C::SLOT_BYTES + (is_b ? BM * 64 : 0) + r0 * 64;
-        const uint16_t* src = (is_b ? b_row[g] + ld_k64 * 64 : a_cur[g]) + h * 32;
-        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(dst) : "memory");
+        const char* base = (is_b ? b_base : a_base) + h * 64;
+        const unsigned voff = is_b ? b_voff[g] : a_voff[g];
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(dst) : "memory");
     };
     auto advance_pair = [&]() {
-#pragma unroll
-        for (int g = 0; g < C::GA; ++g) a_cur[g] += 64;
-        if (++ld_k64 == n_k64) { ld_k64 = 0; ++ld_vt; point_at_tile(ld_vt); }
+        a_base += 128;
+        b_base += 128;
+        if (++ld_k64 == n_k64) {   // next vocabulary tile: W moves on by a tile minus the row just walked, H rewinds
+            ld_k64 = 0;
+            ++ld_vt;
+            a_base += tile_bytes - row_bytes;
+            b_base -= row_bytes;
+            point_at_tile(ld_vt);
+        }
         ld_slot = ld_slot + 2 >= RING ? ld_slot + 2 - RING : ld_slot + 2;
     };
     auto issue_pair = [&]() {
@@ -439,10 +457,10 @@ __global__ __launch_bounds__(C::NT) void logprob_ring_kernel(LogprobArgs a) {
         if (r < TN) fb[r] = *reinterpret_cast<const bf16x8*>(base + b_off + r * 32 * 64);
         else if (r < TN + TM) fa[r - TN] = *reinterpret_cast<const bf16x8*>(base + a_off + (r - TN) * 32 * 64);
     };
-    auto iteration = [&](bool loads) {
+    auto iteration = [&](const bool LOADS) {   // wave-uniform
         // this wave's LDS reads are complete before it tells the others that their slots may be refilled
         __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0) only
-        if (!(a.probe & 8)) __syncthreads();
+        __syncthreads();
         const unsigned char* base = lds + slot * C::SLOT_BYTES;
         slot = slot + 1 == RING ? 0 : slot + 1;
         const unsigned char* next = lds + slot * C::SLOT_BYTES;
@@ -453,9 +471,9 @@ __global__ __launch_bounds__(C::NT) void logprob_ring_kernel(LogprobArgs a) {
                 __builtin_amdgcn_sched_barrier(0);
                 read_frag(fa1, fb1, base, a_off1, b_off1, x - 1);
                 read_frag(fa1, fb1, base, a_off1, b_off1, x);
+                if (LOADS && (x + 1) % EVERY == 0) issue_one((x + 1) / EVERY - 1);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if ((x + 1) % EVERY == 0 && loads) issue_one((x + 1) / EVERY - 1);
         }
 #pragma unroll
         for (int x = 0; x < NMMA; ++x) {
@@ -464,26 +482,29 @@ __global__ __launch_bounds__(C::NT) void logprob_ring_kernel(LogprobArgs a) {
                 __builtin_amdgcn_sched_barrier(0);
                 read_frag(fa0, fb0, next, a_off0, b_off0, x - 1);
                 read_frag(fa0, fb0, next, a_off0, b_off0, x);
+                if (LOADS && (x + 1) % EVERY == 0) issue_one(NMMA / EVERY + (x + 1) / EVERY - 1);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if ((x + 1) % EVERY == 0 && loads) issue_one(NMMA / EVERY + (x + 1) / EVERY - 1);
         }
-        if (loads) advance_pair();
+        if (LOADS) advance_pair();
     };
+    static_assert(EVERY % 2 == 0, "loads are issued next to the fragment reads, after odd MFMAs");
     for (int i = 0; i < n_chunks; i += 2) {
-        // even iteration: chunk i+1 belongs to the pair of chunk i (already certified); the pair requested
-        // during iteration i-1 may stay in flight
-        if (a.probe & 1) {} else if ((i >> 1) + 1 < issued) wait_vmcnt<C::LOADS_PER_PAIR>(); else wait_vmcnt<0>();
+        // Before the barrier of iteration i this wave's part of chunk i+1 must have landed.
+        // Even i: chunk i+1 shares the pair of chunk i (certified one iteration ago); only the pair
+        // requested during iteration i-1 may still be in flight.
+        if ((i >> 1) + 1 < issued) wait_vmcnt<C::LOADS_PER_PAIR>(); else wait_vmcnt<0>();
         iteration(false);
-        // odd iteration: chunk i+2 opens the next pair: everything requested so far must have landed;
-        // slots i-1 and i (= i+4, i+5 mod RING) are free after its barrier and take the next pair
-        if (!(a.probe & 1)) wait_vmcnt<0>();
-        const bool loads = issued < n_pairs && !(a.probe & 2);
+        // Odd i+1: chunk i+2 opens the next pair, requested two iterations ago, and nothing younger
+        // exists: wait for everything.  The iteration then requests the pair after that into slots
+        // i-1 and i (= i+4, i+5 mod RING), both fully read before its barrier.
+        wait_vmcnt<0>();
+        const bool loads = issued < n_pairs;
         iteration(loads);
         issued += loads ? 1 : 0;
         kc += 2;
         if (kc == n_kc) {   // a tile ends on an odd chunk (d is a multiple of 64)
-            if (!(a.probe & 4)) tile_epilogue<TM, TN, BM / C::WM>(acc, st, vt * BM + wm * (BM / C::WM), a.V, lh);
+            tile_epilogue<TM, TN, BM / C::WM>(acc, st, vt * BM + wm * (BM / C::WM), a.V, lh);
             kc = 0;
             ++vt;
         }
@@ -520,7 +541,6 @@ static_assert(MainTile::BM == FastTile::BM && MainTile::BN == FastTile::BN, "one
 
 int g_force_splits = 0;  // 0 = heuristic
 int g_force_general = 0; // 1 = use the general kernel even when d % 64 == 0
-int g_probe = 0;
 
 struct Plan { int n_tb, n_vt, n_sp; };
 
@@ -547,7 +567,6 @@ extern "C" int arrol_set_tuning(const char* key, int value) {
     if (!key) return ARROL_EINVAL;
     if (!__builtin_strcmp(key, "logprob_splits")) { g_force_splits = value; return ARROL_OK; }
     if (!__builtin_strcmp(key, "logprob_general_kernel")) { g_force_general = value; return ARROL_OK; }
-    if (!__builtin_strcmp(key, "logprob_probe")) { g_probe = value; return ARROL_OK; }
     return ARROL_EINVAL;
 }
 
@@ -586,7 +605,6 @@ extern "C" int arrol_logprob(const void* hidden, const void* lm_head, const int3
     a.part = static_cast<float*>(workspace);
     a.T = T; a.V = V; a.d = d;
     a.n_tb = p.n_tb; a.n_sp = p.n_sp; a.n_vt = p.n_vt;
-    a.probe = g_probe;
     const int tb_pad = (p.n_tb + kXcds - 1) / kXcds * kXcds;
     if (d % 64 == 0 && !g_force_general)
         hipLaunchKernelGGL(logprob_ring_kernel<FastTile>, dim3(tb_pad * p.n_sp), dim3(FastTile::NT), FastTile::LDS_BYTES, st, a);
