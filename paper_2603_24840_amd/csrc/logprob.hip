@@ -290,9 +290,23 @@ __global__ __launch_bounds__(C::NT) void logprob_kernel(LogprobArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Fast kernel (d a multiple of 64): global -> LDS directly (no staging registers), a ring of
-// RING K32 slots.  Loads are issued two slots at a time, i.e. as whole 128-byte lines of every
-// tile row, three slot-times ahead of their use.
+// Fast kernel (d a multiple of 64): global -> LDS directly (no staging registers) into a ring of
+// RING K32 slots (32 k-values = 64 bytes of each of the BM + BN tile rows).
+//
+// Loads always fetch whole 128-byte lines of a row, i.e. the two K32 halves that go to two
+// consecutive slots (a "pair").  The L1 path moves 64 bytes per clock, so a pair costs as many L1
+// cycles as half of its MFMA time; to keep that evenly spread, the W lines ("A") of a pair are
+// requested during one K32 iteration and its H lines ("B") during the next.  The pipeline per
+// iteration i (chunk i lives in slot i % RING):
+//   K16 step 0: MFMAs on fragments already in registers; between them the step-1 fragment reads of
+//               slot i and two of this iteration's four load instructions;
+//   K16 step 1: MFMAs; between them the step-0 reads of the W fragments of slot i+1 (certified one
+//               barrier earlier), then - four MFMAs before the end - the wait for this wave's older
+//               loads and the workgroup barrier, then the step-0 reads of the H fragments of slot i+1
+//               and the remaining loads.  The last MFMAs cover the latency of those reads, so the
+//               matrix pipe never waits for an LDS round trip behind a barrier.
+// The barrier inside iteration i certifies the W part of slot i+2 and the H part of slot i+1 and
+// releases slot i-1 (W lines) / slot i-2.. for refilling; see the table in the loop for who loads what.
 // ---------------------------------------------------------------------------------------------
 template <int BM_, int BN_, int WM_, int WN_>
 struct RingTile {
@@ -301,13 +315,13 @@ struct RingTile {
     static constexpr int NW = WM * WN;
     static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     static constexpr int RING = 5;
-    static constexpr int SLOT_BYTES = (BM + BN) * 64;      // 32 k-values (64 bytes) of every tile row
+    static constexpr int SLOT_BYTES = (BM + BN) * 64;
     static constexpr int LDS_BYTES = RING * SLOT_BYTES;
-    static constexpr int GA = BM / 16 / NW;                 // 16-row load groups of the W tile per wave
-    static constexpr int GB = BN / 16 / NW;
-    static constexpr int LOADS_PER_PAIR = 2 * (GA + GB);    // load instructions a wave issues per slot pair
-    static_assert(BM % (16 * NW) == 0 && BN % (16 * NW) == 0, "whole 16-row load groups per wave");
-    static_assert(LOADS_PER_PAIR <= 15, "the vmcnt immediate used below");
+    static constexpr int G = BM / 16 / NW;                  // 16-row load groups per wave and operand
+    static constexpr int LOADS = 2 * G;                     // load instructions per wave and iteration
+    static_assert(BM == BN, "W and H tiles are loaded by the same code in alternate iterations");
+    static_assert(BM % (16 * NW) == 0, "whole 16-row load groups per wave");
+    static_assert(LOADS == 4 && TM * TN == 8 && TM + TN <= 8, "the hand-placed schedule below");
 };
 
 template <int N>
@@ -330,7 +344,8 @@ __global__ __launch_bounds__(C::NT) void logprob_ring_kernel(LogprobArgs a) {
     const int l31 = lane & 31, lh = lane >> 5;
     const int64_t tok0 = static_cast<int64_t>(tb) * BN;
     const int n_k64 = a.d / 64;
-    const int n_pairs = (vt_hi - vt_lo) * n_k64;     // one pair = two K32 slots = one 128-byte line per row
+    // (readfirstlane: wave-uniform by construction; it keeps the loop control in scalar registers)
+    const int n_pairs = __builtin_amdgcn_readfirstlane((vt_hi - vt_lo) * n_k64);   // pair = two K32 slots = one 128-byte line per row
     const int n_chunks = 2 * n_pairs;
 
     // ---- loader geometry: one instruction moves 16 rows x 64 bytes; lane -> (row lane/4, physical
@@ -341,12 +356,13 @@ __global__ __launch_bounds__(C::NT) void logprob_ring_kernel(LogprobArgs a) {
     // carries tile and K position, the lane offset the row inside the tile (clamped at the end of the
     // vocabulary / token range, so every load stays inside W and H) and the swizzled chunk.
     const int64_t row_bytes = static_cast<int64_t>(a.d) * 2;
-    unsigned a_voff[C::GA], b_voff[C::GB];
+    const int64_t tile_bytes = BM * row_bytes;
+    unsigned a_voff[C::G], b_voff[C::G];
     {
         const int64_t rows_valid = a.T - tok0 < BN ? a.T - tok0 : BN;
 #pragma unroll
-        for (int g = 0; g < C::GB; ++g) {
-            int64_t r = (wave * C::GB + g) * 16 + ld_row;
+        for (int g = 0; g < C::G; ++g) {
+            int64_t r = (wave * C::G + g) * 16 + ld_row;
             r = r < rows_valid ? r : rows_valid - 1;
             b_voff[g] = static_cast<unsigned>(r * row_bytes + ld_kb);
         }
@@ -355,50 +371,60 @@ __global__ __launch_bounds__(C::NT) void logprob_ring_kernel(LogprobArgs a) {
         const int64_t left = static_cast<int64_t>(a.V) - static_cast<int64_t>(vt) * BM;
         const int64_t rows_valid = left < BM ? (left > 0 ? left : 1) : BM;   // left <= 0 only past the last pair
 #pragma unroll
-        for (int g = 0; g < C::GA; ++g) {
-            int64_t r = (wave * C::GA + g) * 16 + ld_row;
+        for (int g = 0; g < C::G; ++g) {
+            int64_t r = (wave * C::G + g) * 16 + ld_row;
             r = r < rows_valid ? r : rows_valid - 1;
             a_voff[g] = static_cast<unsigned>(r * row_bytes + ld_kb);
         }
     };
-    int ld_vt = vt_lo, ld_k64 = 0, ld_slot = 0;
-    point_at_tile(ld_vt);
-    const unsigned lds0 = static_cast<unsigned>(reinterpret_cast<size_t>((lds_ptr_t)lds));
-    // uniform bases of the next pair to load: W tile ld_vt / H token block, at K position ld_k64*64
-    const int64_t tile_bytes = BM * row_bytes;
-    const char* a_base = reinterpret_cast<const char*>(a.W) + ld_vt * tile_bytes;
+    // two load streams, each walking the pairs 0 .. n_pairs-1: W lines (A) and H lines (B)
+    int a_vt = vt_lo, a_k64 = 0, a_slot = 0, a_issued = 0;
+    int b_k64 = 0, b_slot = 0, b_issued = 0;
+    const char* a_base = reinterpret_cast<const char*>(a.W) + a_vt * tile_bytes;
     const char* b_base = reinterpret_cast<const char*>(a.H) + tok0 * row_bytes;
-    // The q-th of the LOADS_PER_PAIR load instructions this wave contributes to a slot pair:
-    // q = 2*g + h for the W rows (g < GA), 2*GA + 2*g + h for the H rows; h picks the K32 half / slot.
-    // Written as asm so that the compiler keeps its own LDS wait counters exact; completion is
-    // tracked by hand with s_waitcnt vmcnt + the workgroup barrier.
-    auto issue_one = [&](int q) {
-        const bool is_b = q >= 2 * C::GA;
-        const int g = (is_b ? q - 2 * C::GA : q) >> 1, h = q & 1;
-        const int s_h = h == 0 ? ld_slot : (ld_slot + 1 == RING ? 0 : ld_slot + 1);
-        const int r0 = (wave * (is_b ? C::GB : C::GA) + g) * 16;
+    point_at_tile(a_vt);
+    const unsigned lds0 = static_cast<unsigned>(reinterpret_cast<size_t>((lds_ptr_t)lds));
+    // The q-th (q = 2*g + h) of the LOADS load instructions of a group: 16-row group g of this wave, K32
+    // half h (-> first / second slot of the pair).  `stream` picks W lines or H lines at compile time.  Written as asm
+    // so that the compiler keeps its own LDS wait counters exact; completion is tracked by hand with
+    // s_waitcnt vmcnt + the workgroup barrier.
+    auto issue_one = [&](auto stream, int q) {
+        constexpr bool is_b = decltype(stream)::value;
+        const int g = q >> 1, h = q & 1;
+        const int slot0 = is_b ? b_slot : a_slot;
+        const int s_h = h == 0 ? slot0 : (slot0 + 1 == RING ? 0 : slot0 + 1);
+        const int r0 = (wave * C::G + g) * 16;
         const unsigned dst = lds0 + s_h * C::SLOT_BYTES + (is_b ? BM * 64 : 0) + r0 * 64;
         const char* base = (is_b ? b_base : a_base) + h * 64;
         const unsigned voff = is_b ? b_voff[g] : a_voff[g];
         asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(dst) : "memory");
     };
-    auto advance_pair = [&]() {
-        a_base += 128;
-        b_base += 128;
-        if (++ld_k64 == n_k64) {   // next vocabulary tile: W moves on by a tile minus the row just walked, H rewinds
-            ld_k64 = 0;
-            ++ld_vt;
-            a_base += tile_bytes - row_bytes;
-            b_base -= row_bytes;
-            point_at_tile(ld_vt);
+    auto advance = [&](auto stream) {
+        constexpr bool is_b = decltype(stream)::value;
+        if (is_b) {
+            b_base += 128;
+            if (++b_k64 == n_k64) { b_k64 = 0; b_base -= row_bytes; }   // next vocabulary tile: H rewinds
+            b_slot = b_slot + 2 >= RING ? b_slot + 2 - RING : b_slot + 2;
+            ++b_issued;
+        } else {
+            a_base += 128;
+            if (++a_k64 == n_k64) {   // next vocabulary tile: W moves on by a tile minus the row just walked
+                a_k64 = 0;
+                ++a_vt;
+                a_base += tile_bytes - row_bytes;
+                point_at_tile(a_vt);
+            }
+            a_slot = a_slot + 2 >= RING ? a_slot + 2 - RING : a_slot + 2;
+            ++a_issued;
         }
-        ld_slot = ld_slot + 2 >= RING ? ld_slot + 2 - RING : ld_slot + 2;
     };
-    auto issue_pair = [&]() {
+    auto issue_group = [&](auto stream) {
 #pragma unroll
-        for (int q = 0; q < C::LOADS_PER_PAIR; ++q) issue_one(q);
-        advance_pair();
+        for (int q = 0; q < C::LOADS; ++q) issue_one(stream, q);
+        advance(stream);
     };
+    constexpr std::false_type kA{};   // W lines
+    constexpr std::true_type kB{};    // H lines
 
     LaneState<TN> st;
 #pragma unroll
@@ -422,94 +448,103 @@ __global__ __launch_bounds__(C::NT) void logprob_ring_kernel(LogprobArgs a) {
     const int b_off0 = BM * 64 + (wn * (BN / C::WN) + l31) * 64 + ((lh ^ swz) << 4);
     const int b_off1 = BM * 64 + (wn * (BN / C::WN) + l31) * 64 + (((2 + lh) ^ swz) << 4);
     bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];   // fragments of K16 step 0 / step 1
-    auto read_step0 = [&](const unsigned char* base) {
-#pragma unroll
-        for (int j = 0; j < TN; ++j) fb0[j] = *reinterpret_cast<const bf16x8*>(base + b_off0 + j * 32 * 64);
-#pragma unroll
-        for (int m = 0; m < TM; ++m) fa0[m] = *reinterpret_cast<const bf16x8*>(base + a_off0 + m * 32 * 64);
+    auto read_a = [&](bf16x8 (&fa)[TM], const unsigned char* base, int off, int m) {
+        fa[m] = *reinterpret_cast<const bf16x8*>(base + off + m * 32 * 64);
+    };
+    auto read_b = [&](bf16x8 (&fb)[TN], const unsigned char* base, int off, int j) {
+        fb[j] = *reinterpret_cast<const bf16x8*>(base + off + j * 32 * 64);
+    };
+    auto mma = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], int x) {
+        acc[x / TN][x % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[x / TN], fb[x % TN], acc[x / TN][x % TN], 0, 0, 0);
     };
 
-    // Pipeline.  Chunk c lives in ring slot c % RING.  Pair p = chunks (2p, 2p+1) is requested during
-    // the odd iteration 2p-3 (pairs 0 and 1 up front), its loads interleaved with that iteration's
-    // MFMAs.  The barrier that opens iteration i certifies chunk i+1 (every wave has waited for its own
-    // part), because step 0 of chunk i+1 is read into registers during iteration i, so that the MFMAs
-    // after the next barrier start without an LDS round trip.
-    if (n_pairs > 0) issue_pair();
-    if (n_pairs > 1) issue_pair();
-    int issued = n_pairs < 2 ? n_pairs : 2;
+    // Load schedule (pair p = chunks 2p, 2p+1 -> slots 2p % RING, (2p+1) % RING):
+    //   up front           A(0), B(0), A(1)
+    //   iteration 2p-2     B(p)   (even iterations, p >= 1)
+    //   iteration 2p-3     A(p)   (odd iterations,  p >= 2)
+    // The barrier inside iteration i needs every group requested before iteration i to have landed
+    // (W part of slot i+2, H part of slot i+1), i.e. only this iteration's own loads may be in flight.
+    if (n_pairs > 0) { issue_group(kA); issue_group(kB); }
+    if (n_pairs > 1) issue_group(kA);
     if (n_pairs > 0) {
-        if (issued > 1) wait_vmcnt<C::LOADS_PER_PAIR>(); else wait_vmcnt<0>();
+        if (n_pairs > 1) wait_vmcnt<C::LOADS>(); else wait_vmcnt<0>();
         __syncthreads();
-        read_step0(lds);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) read_b(fb0, lds, b_off0, j);
+#pragma unroll
+        for (int m = 0; m < TM; ++m) read_a(fa0, lds, a_off0, m);
     }
     int vt = vt_lo, kc = 0, slot = 0;
     const int n_kc = 2 * n_k64;
-    constexpr int NMMA = TM * TN;                         // MFMAs per K16 step
-    constexpr int EVERY = 2 * NMMA / C::LOADS_PER_PAIR;    // one load after every EVERY-th MFMA
-    static_assert(EVERY >= 1 && 2 * NMMA % C::LOADS_PER_PAIR == 0, "loads spread evenly over the MFMAs");
-    // One K32 chunk: 2 x NMMA MFMAs.  Everything else is threaded between the MFMAs so that the matrix
-    // pipe always has the next instruction waiting: after every 2nd MFMA of K16 step 0 two fragment reads
-    // of this slot's step 1, after every 2nd MFMA of step 1 two reads of the NEXT slot's step 0 (after the
-    // last chunk that is a stale slot; never used), and, when `loads` (wave-uniform) is set, one of this
-    // wave's LOADS_PER_PAIR global->LDS loads of the next slot pair after every EVERY-th MFMA.
-    static_assert(TM + TN <= NMMA && NMMA % 2 == 0, "fragment reads fit between the MFMAs of one step");
-    auto read_frag = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], const unsigned char* base, int a_off, int b_off, int r) {
-        if (r < TN) fb[r] = *reinterpret_cast<const bf16x8*>(base + b_off + r * 32 * 64);
-        else if (r < TN + TM) fa[r - TN] = *reinterpret_cast<const bf16x8*>(base + a_off + (r - TN) * 32 * 64);
-    };
-    auto iteration = [&](const bool LOADS) {   // wave-uniform
-        // this wave's LDS reads are complete before it tells the others that their slots may be refilled
+    // `always` = std::true_type: steady state, the iteration's four loads are unconditional (no branches
+    // between the MFMAs); std::false_type: drain, loads only while the stream still has pairs to request.
+    auto iteration = [&](auto stream, auto always) {
+        constexpr bool is_b = decltype(stream)::value;
+        const unsigned char* cur = lds + slot * C::SLOT_BYTES;
+        slot = slot + 1 == RING ? 0 : slot + 1;
+        const unsigned char* nxt = lds + slot * C::SLOT_BYTES;
+        const bool loads = decltype(always)::value || (is_b ? b_issued : a_issued) < n_pairs;   // wave-uniform
+        // ---- K16 step 0 -------------------------------------------------------------------------
+        mma(fa0, fb0, 0); mma(fa0, fb0, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        read_b(fb1, cur, b_off1, 0); read_b(fb1, cur, b_off1, 1);
+        if (loads) issue_one(stream, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(fa0, fb0, 2); mma(fa0, fb0, 3);
+        __builtin_amdgcn_sched_barrier(0);
+        read_a(fa1, cur, a_off1, 0); read_a(fa1, cur, a_off1, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(fa0, fb0, 4); mma(fa0, fb0, 5);
+        __builtin_amdgcn_sched_barrier(0);
+        read_a(fa1, cur, a_off1, 2); read_a(fa1, cur, a_off1, 3);
+        if (loads) issue_one(stream, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(fa0, fb0, 6); mma(fa0, fb0, 7);
+        __builtin_amdgcn_sched_barrier(0);
+        // ---- K16 step 1 -------------------------------------------------------------------------
+        mma(fa1, fb1, 0); mma(fa1, fb1, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        read_a(fa0, nxt, a_off0, 0); read_a(fa0, nxt, a_off0, 1);           // W part of slot i+1: certified already
+        if (loads) issue_one(stream, 2);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(fa1, fb1, 2); mma(fa1, fb1, 3);
+        __builtin_amdgcn_sched_barrier(0);
+        // everything this wave requested before this iteration has landed (3 younger loads may fly);
+        // its own LDS reads are complete; then all waves agree
+        if (loads) wait_vmcnt<3>(); else wait_vmcnt<0>();
         __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0) only
         __syncthreads();
-        const unsigned char* base = lds + slot * C::SLOT_BYTES;
-        slot = slot + 1 == RING ? 0 : slot + 1;
-        const unsigned char* next = lds + slot * C::SLOT_BYTES;
-#pragma unroll
-        for (int x = 0; x < NMMA; ++x) {
-            acc[x / TN][x % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[x / TN], fb0[x % TN], acc[x / TN][x % TN], 0, 0, 0);
-            if (x & 1) {
-                __builtin_amdgcn_sched_barrier(0);
-                read_frag(fa1, fb1, base, a_off1, b_off1, x - 1);
-                read_frag(fa1, fb1, base, a_off1, b_off1, x);
-                if (LOADS && (x + 1) % EVERY == 0) issue_one((x + 1) / EVERY - 1);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-#pragma unroll
-        for (int x = 0; x < NMMA; ++x) {
-            acc[x / TN][x % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[x / TN], fb1[x % TN], acc[x / TN][x % TN], 0, 0, 0);
-            if (x & 1) {
-                __builtin_amdgcn_sched_barrier(0);
-                read_frag(fa0, fb0, next, a_off0, b_off0, x - 1);
-                read_frag(fa0, fb0, next, a_off0, b_off0, x);
-                if (LOADS && (x + 1) % EVERY == 0) issue_one(NMMA / EVERY + (x + 1) / EVERY - 1);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-        if (LOADS) advance_pair();
+        read_b(fb0, nxt, b_off0, 0); read_b(fb0, nxt, b_off0, 1);           // H part of slot i+1: certified just now
+        read_a(fa0, nxt, a_off0, 2); read_a(fa0, nxt, a_off0, 3);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(fa1, fb1, 4); mma(fa1, fb1, 5);
+        __builtin_amdgcn_sched_barrier(0);
+        if (loads) { issue_one(stream, 3); advance(stream); }
+        __builtin_amdgcn_sched_barrier(0);
+        mma(fa1, fb1, 6); mma(fa1, fb1, 7);
     };
-    static_assert(EVERY % 2 == 0, "loads are issued next to the fragment reads, after odd MFMAs");
-    for (int i = 0; i < n_chunks; i += 2) {
-        // Before the barrier of iteration i this wave's part of chunk i+1 must have landed.
-        // Even i: chunk i+1 shares the pair of chunk i (certified one iteration ago); only the pair
-        // requested during iteration i-1 may still be in flight.
-        if ((i >> 1) + 1 < issued) wait_vmcnt<C::LOADS_PER_PAIR>(); else wait_vmcnt<0>();
-        iteration(false);
-        // Odd i+1: chunk i+2 opens the next pair, requested two iterations ago, and nothing younger
-        // exists: wait for everything.  The iteration then requests the pair after that into slots
-        // i-1 and i (= i+4, i+5 mod RING), both fully read before its barrier.
-        wait_vmcnt<0>();
-        const bool loads = issued < n_pairs;
-        iteration(loads);
-        issued += loads ? 1 : 0;
+    auto end_of_pair = [&]() {
         kc += 2;
         if (kc == n_kc) {   // a tile ends on an odd chunk (d is a multiple of 64)
             tile_epilogue<TM, TN, BM / C::WM>(acc, st, vt * BM + wm * (BM / C::WM), a.V, lh);
             kc = 0;
             ++vt;
         }
+    };
+    // even iteration i requests the H lines of pair i/2 + 1, odd iteration i+1 the W lines of pair i/2 + 2
+    int i = 0;
+    for (; i < n_chunks && a_issued < n_pairs; i += 2) {   // steady state (the W stream runs one pair ahead)
+        iteration(kB, std::true_type{});
+        iteration(kA, std::true_type{});
+        end_of_pair();
+    }
+    for (; i < n_chunks; i += 2) {                          // drain: the last two pairs
+        iteration(kB, std::false_type{});
+        iteration(kA, std::false_type{});
+        end_of_pair();
     }
     wait_vmcnt<0>();
+    __builtin_amdgcn_s_waitcnt(0xC07F);
     __syncthreads();   // every fragment read and every load into LDS has finished
     write_partials<TN, C::WM, C::WN, BN, C::NT>(st, reinterpret_cast<float*>(lds), wm, wn, l31, lh, tid, tok0,
                                                  a.T, sp, a.part);
