@@ -23,7 +23,10 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak, published
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs scaled by the plain-copy calibration (profiles/); None where not measured.
-PROFILED_TRAFFIC_BYTES = {}
+PROFILED_TRAFFIC_BYTES = {
+    ("llama1b", "logprob"): 2.7727e11,   # profiles/hbm_traffic_llama1b.txt (fabric-level fetch incl. Infinity-Cache hits)
+    ("llama1b", "compact"): 8.593e9,
+}
 
 
 def parse():
