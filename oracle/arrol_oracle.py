@@ -18,6 +18,7 @@ Stages (paper passages in each docstring):
   compact        survivor gather / re-batch        Sec. 4.3 (i),(ii); Alg. 1
   logprob        log pi(o_t | o_<t)                Sec. 3 (GRPO ratio); Alg. 1
   weighted_vote  rank-weighted answer vote         Sec. 4.4
+  histogram / calibrate / prune_bernoulli   the practical policy   App. A.4 Eq. 1-2; Alg. 1
 """
 import math
 
@@ -246,3 +247,103 @@ def weighted_vote(prob_f32, answer_id, n_questions, C, A):
                 best = a
         winner[u] = best
     return winner, tally
+
+
+# ----------------------------------------------------------------------------
+# the paper's practical pruning policy (App. A.4; Alg. 1 backend lines)
+# ----------------------------------------------------------------------------
+def bin_index(s_norm_f32, B):
+    """Uniform bin of a normalised score, b(s') = min(B-1, floor(B * s')) (App. A.4).  The product is
+    taken in fp32 (exact for B a power of two), which is where both sides take the decision."""
+    s = np.asarray(s_norm_f32, dtype=np.float32)
+    b = np.floor(s * np.float32(B)).astype(np.int64)
+    return np.minimum(B - 1, np.maximum(0, b))
+
+
+def histogram(s_norm_f32, label, B):
+    """Histogram counts of the two labelled buffers (App. A.4 Eq. 1):
+    c_b^+ = #{k : b(s_k^+) = b},  c_b^- = #{k : b(s_k^-) = b}."""
+    b = bin_index(s_norm_f32, B)
+    lab = np.asarray(label).astype(bool)
+    c_pos = np.zeros(B, dtype=np.int64)
+    c_neg = np.zeros(B, dtype=np.int64)
+    for k in range(len(b)):
+        if lab[k]:
+            c_pos[b[k]] += 1
+        else:
+            c_neg[b[k]] += 1
+    return c_pos, c_neg
+
+
+def posterior_lut(c_pos, c_neg, alpha):
+    """Binned posterior q(b) = P(Y=1 | b) by Bayes' rule with Laplace-smoothed likelihoods (App. A.4):
+        P(b|Y=1) = (c_b^+ + alpha) / (sum_b' c_b'^+ + alpha B),  same for Y=0,
+        q(b) = pi P(b|1) / (pi P(b|1) + (1-pi) P(b|0)),  pi = P(Y=1) estimated from the buffers.
+    Reading: pi = N^+ / (N^+ + N^-), 1/2 when both buffers are empty."""
+    c_pos = np.asarray(c_pos, dtype=np.float64)
+    c_neg = np.asarray(c_neg, dtype=np.float64)
+    B = len(c_pos)
+    n_pos, n_neg = c_pos.sum(), c_neg.sum()
+    pi = 0.5 if n_pos + n_neg == 0 else n_pos / (n_pos + n_neg)
+    like_pos = (c_pos + alpha) / (n_pos + alpha * B)
+    like_neg = (c_neg + alpha) / (n_neg + alpha * B)
+    num = pi * like_pos
+    den = num + (1.0 - pi) * like_neg
+    q = np.where(den > 0, num / np.where(den > 0, den, 1.0), pi)
+    return q, pi
+
+
+def bin_weights(c_pos, c_neg):
+    """The buffer distribution over bins used for the expectation E[p]: w_b = (c_b^+ + c_b^-)/total,
+    uniform when the buffers are empty."""
+    tot = np.asarray(c_pos, dtype=np.float64) + np.asarray(c_neg, dtype=np.float64)
+    s = tot.sum()
+    return tot / s if s > 0 else np.full(len(tot), 1.0 / len(tot))
+
+
+def survival_lut(q, w, kappa, rho, lam, p_min, p_max, iters=64):
+    """Survival probability per bin (App. A.4 Eq. 2): p = clip(kappa + delta + lambda (rho - q), p_min, p_max),
+    with the scalar delta found by binary search so that the expected keep rate under the buffer
+    distribution matches kappa: sum_b w_b p_b = kappa.  Reading: the bracket is
+    [p_min - kappa - lambda, p_max - kappa + lambda] (every bin clipped low / high at its ends), `iters`
+    halvings, delta = the final midpoint."""
+    q = np.asarray(q, dtype=np.float64)
+
+    def p_of(delta):
+        return np.clip(kappa + delta + lam * (rho - q), p_min, p_max)
+
+    lo, hi = p_min - kappa - lam, p_max - kappa + lam
+    for _ in range(iters):
+        mid = 0.5 * (lo + hi)
+        if float(np.dot(w, p_of(mid))) < kappa:
+            lo = mid
+        else:
+            hi = mid
+    delta = 0.5 * (lo + hi)
+    return p_of(delta), delta
+
+
+def calibrate(c_pos, c_neg, kappa, rho, lam, p_min, p_max, alpha):
+    """Histogram parameters h_t the frontend sends to the backend (Alg. 1): per-bin posterior q, per-bin
+    survival probability p and the bias delta."""
+    q, _ = posterior_lut(c_pos, c_neg, alpha)
+    p, delta = survival_lut(q, bin_weights(c_pos, c_neg), kappa, rho, lam, p_min, p_max)
+    return q, p, delta
+
+
+def prune_bernoulli(s_norm_f32, uniforms_f32, p_lut_f32):
+    """Backend decision when a rollout first reaches the detection length (Alg. 1): look up its survival
+    probability p_i by the bin of its normalised score and prune it with probability 1 - p_i.  The random
+    numbers are passed in: rollout i survives iff u_i < p_i (both fp32).  Returns p [N] fp32,
+    keep_mask uint8 [N], survivor_idx int32 (ascending), n_survivors."""
+    p_lut = np.asarray(p_lut_f32, dtype=np.float32)
+    b = bin_index(s_norm_f32, len(p_lut))
+    p = p_lut[b]
+    u = np.asarray(uniforms_f32, dtype=np.float32)
+    keep = np.zeros(len(u), dtype=np.uint8)
+    surv = []
+    for i in range(len(u)):
+        if u[i] < p[i]:
+            keep[i] = 1
+            surv.append(i)
+    return p, keep, np.asarray(surv, dtype=np.int32), len(surv)

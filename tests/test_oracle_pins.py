@@ -424,3 +424,126 @@ def test_vote_invariances_and_single_candidate():
     assert np.array_equal(w, w3) and np.array_equal(t, t3)
     w1, t1 = O.weighted_vote(np.array([0.7], np.float32), [3], 1, 1, 5)
     assert w1.tolist() == [3] and t1.sum() == 0      # absent ids never win
+
+
+# ----------------------------------------------------------------------------- practical policy (App. A.4)
+def test_bin_index_edges_and_histogram_brute_force():
+    B = 128
+    s = np.array([0.0, 1.0, 0.5, 127 / 128, 1 / 128, np.nextafter(np.float32(1 / 128), np.float32(0)), 0.999999],
+                 dtype=np.float32)
+    assert O.bin_index(s, B).tolist() == [0, 127, 64, 127, 1, 0, 127]
+    rng = np.random.default_rng(51)
+    s = rng.random(500).astype(np.float32)
+    lab = rng.integers(0, 2, 500)
+    for B in (128, 10, 1):
+        c_pos, c_neg = O.histogram(s, lab, B)
+        assert c_pos.sum() == lab.sum() and c_neg.sum() == 500 - lab.sum()
+        for b in range(B):  # definition with exact rationals: b <= B s' < b+1 (the top edge closed for the last bin)
+            inside = [(Fraction(float(np.float32(x) * np.float32(B))) >= b) and
+                      (Fraction(float(np.float32(x) * np.float32(B))) < b + 1 or b == B - 1) for x in s]
+            assert c_pos[b] == sum(1 for k in range(500) if inside[k] and lab[k])
+            assert c_neg[b] == sum(1 for k in range(500) if inside[k] and not lab[k])
+
+
+def test_posterior_alpha_zero_is_the_empirical_fraction():
+    # with alpha = 0 Bayes' rule collapses: pi P(b|1) = c_b^+ / N, so q(b) = c_b^+ / (c_b^+ + c_b^-)
+    rng = np.random.default_rng(52)
+    c_pos = rng.integers(1, 50, 16)
+    c_neg = rng.integers(1, 50, 16)
+    q, pi = O.posterior_lut(c_pos, c_neg, 0.0)
+    assert np.allclose(q, c_pos / (c_pos + c_neg), rtol=0, atol=1e-15)
+    assert abs(pi - c_pos.sum() / (c_pos.sum() + c_neg.sum())) < 1e-15
+
+
+def test_posterior_uninformative_histograms_return_the_prior():
+    # identical class-conditional histograms carry no information: q(b) = pi in every bin
+    c = np.array([3, 0, 7, 1, 9, 2])
+    q, pi = O.posterior_lut(2 * c, c, 0.0 + 1e-300)
+    assert np.allclose(q[c > 0], 2 / 3, rtol=0, atol=1e-12) and abs(pi - 2 / 3) < 1e-15
+    # heavy smoothing washes the likelihoods out: q -> pi
+    rng = np.random.default_rng(53)
+    c_pos, c_neg = rng.integers(0, 30, 8), rng.integers(0, 30, 8)
+    q, pi = O.posterior_lut(c_pos, c_neg, 1e12)
+    assert np.allclose(q, pi, rtol=0, atol=1e-9)
+    # empty buffers: prior 1/2 everywhere
+    q, pi = O.posterior_lut(np.zeros(4), np.zeros(4), 1.0)
+    assert pi == 0.5 and np.all(q == 0.5)
+    # likelihoods are distributions over bins
+    for a in (0.5, 1.0, 3.0):
+        lp = (c_pos + a) / (c_pos.sum() + a * 8)
+        assert abs(lp.sum() - 1.0) < 1e-15
+
+
+def test_posterior_exact_rational_bayes():
+    c_pos, c_neg, alpha = [5, 0, 2], [1, 4, 0], Fraction(1, 2)
+    q, _ = O.posterior_lut(c_pos, c_neg, float(alpha))
+    B, n_pos, n_neg = 3, sum(c_pos), sum(c_neg)
+    pi = Fraction(n_pos, n_pos + n_neg)
+    for b in range(B):
+        l1 = (c_pos[b] + alpha) / (n_pos + alpha * B)
+        l0 = (c_neg[b] + alpha) / (n_neg + alpha * B)
+        assert abs(q[b] - float(pi * l1 / (pi * l1 + (1 - pi) * l0))) < 1e-15
+
+
+def test_survival_closed_form_without_clipping():
+    # if no bin is clipped, E[kappa + delta + lambda (rho - q)] = kappa gives delta = lambda (E[q] - rho)
+    rng = np.random.default_rng(54)
+    q = rng.uniform(0.3, 0.7, 32)
+    w = rng.random(32); w /= w.sum()
+    p, delta = O.survival_lut(q, w, kappa=0.5, rho=0.5, lam=0.5, p_min=0.0, p_max=1.0)
+    assert abs(delta - 0.5 * (float(np.dot(w, q)) - 0.5)) < 1e-12
+    assert np.allclose(p, 0.5 + delta + 0.5 * (0.5 - q), rtol=0, atol=1e-12)
+    assert abs(float(np.dot(w, p)) - 0.5) < 1e-12
+    # lambda = 0: every rollout survives with probability kappa, delta = 0
+    p, delta = O.survival_lut(q, w, 0.25, 0.5, 0.0, 0.05, 0.95)
+    assert abs(delta) < 1e-12 and np.allclose(p, 0.25, rtol=0, atol=1e-12)
+
+
+def test_survival_with_clipping_keeps_the_rate_and_the_order():
+    rng = np.random.default_rng(55)
+    for _ in range(50):
+        B = 128
+        q = rng.beta(0.4, 0.4, B)
+        w = rng.random(B) ** 3; w /= w.sum()
+        kappa, rho, lam = rng.choice([0.25, 0.5, 0.75]), rng.choice([0.3, 0.5]), rng.choice([0.5, 1.0, 2.0])
+        p_min, p_max = 0.05, 0.95
+        p, delta = O.survival_lut(q, w, kappa, rho, lam, p_min, p_max)
+        assert np.all(p >= p_min) and np.all(p <= p_max)
+        assert abs(float(np.dot(w, p)) - kappa) < 1e-9                  # expected keep rate = kappa
+        order = np.argsort(q)
+        assert np.all(np.diff(p[order]) <= 1e-15)                       # monotone: likelier-correct rollouts are kept less
+        # brute force: delta is a root of the (monotone) keep-rate curve
+        f = lambda d: float(np.dot(w, np.clip(kappa + d + lam * (rho - q), p_min, p_max))) - kappa
+        assert f(delta - 1e-6) <= 1e-9 and f(delta + 1e-6) >= -1e-9
+    # unattainable target: kappa below p_min -> everything clipped at p_min
+    p, _ = O.survival_lut(q, w, 0.01, 0.5, 0.5, 0.05, 0.95)
+    assert np.allclose(p, 0.05, rtol=0, atol=1e-9)
+
+
+def test_calibrate_composes_and_tilts_toward_low_posteriors():
+    # rollouts with a high posterior get a lower survival probability than those with a low one
+    c_pos = np.array([1, 2, 4, 8, 16, 32, 64, 128])
+    c_neg = c_pos[::-1].copy()
+    q, p, delta = O.calibrate(c_pos, c_neg, 0.5, 0.5, 0.5, 0.05, 0.95, 1.0)
+    assert np.all(np.diff(q) > 0) and np.all(np.diff(p) < 0)
+    w = O.bin_weights(c_pos, c_neg)
+    assert abs(float(np.dot(w, p)) - 0.5) < 1e-9
+    # p falls as q rises, so the kept set can only hold a lower share of likely-correct rollouts than the
+    # population (Chebyshev's sum inequality); nothing in Eq. 2 stops it from overshooting rho
+    kept_pos_rate = float(np.dot(w * p, q) / np.dot(w, p))
+    assert kept_pos_rate <= float(np.dot(w, q)) + 1e-12
+
+
+def test_prune_bernoulli_decisions_and_rate():
+    rng = np.random.default_rng(56)
+    B = 128
+    p_lut = np.linspace(0.9, 0.1, B).astype(np.float32)
+    s = rng.random(2000).astype(np.float32)
+    u = rng.random(2000).astype(np.float32)
+    p, keep, surv, n = O.prune_bernoulli(s, u, p_lut)
+    assert np.array_equal(p, p_lut[np.minimum(B - 1, np.floor(s * 128).astype(int))])
+    assert n == int(keep.sum()) == len(surv) and np.array_equal(surv, np.flatnonzero(u < p))
+    assert abs(n / 2000 - 0.5) < 0.05                                  # E[p] = 0.5 under uniform scores
+    _, keep0, _, n0 = O.prune_bernoulli(s, np.zeros(2000, np.float32), p_lut)
+    _, keep1, _, n1 = O.prune_bernoulli(s, np.ones(2000, np.float32), p_lut)
+    assert n0 == 2000 and n1 == 0
