@@ -8,6 +8,8 @@
  *   arrol_compact        gather survivors' paged KV cache / tokens, re-batch  (Sec. 4.3 (i),(ii); Alg. 1)
  *   arrol_logprob        per-token log pi(o_t | o_<t) on the survivors        (Sec. 3 GRPO ratio; Sec. 4.3 (ii); Alg. 1)
  *   arrol_weighted_vote  rank-weighted answer vote for test-time scaling      (Sec. 4.4)
+ * plus the paper's practical stochastic policy: arrol_histogram, arrol_calibrate, arrol_prune_bernoulli
+ *                                                                               (App. A.4 Eq. 1-2; Alg. 1)
  *
  * Conventions common to every call
  *   - Every data pointer is a DEVICE pointer owned by the caller (the library never
@@ -146,6 +148,55 @@ int arrol_logprob(const void* hidden, const void* lm_head, const int32_t* target
 int arrol_weighted_vote(const float* prob, const int32_t* answer_id, int32_t n_questions,
                         int32_t C, int32_t n_answers, int32_t* winner, int64_t* tally,
                         void* stream);
+
+/*
+ * ---- The paper's practical (stochastic) pruning policy: App. A.4, Eq. 1-2; Alg. 1 backend --------------
+ * The frontend turns its labelled score buffers into histogram parameters; the backend looks up a
+ * survival probability for each rollout that reaches the detection length and prunes it with
+ * probability 1 - p.  Unlike arrol_select the number of survivors is random (kappa*N in expectation).
+ */
+#define ARROL_MAX_BINS 2048
+
+/*
+ * App. A.4 Eq. 1: c_b^+ = #{k : label_k = 1, b(s_k) = b},  c_b^- likewise for label 0, with the uniform
+ * bin b(s') = min(B-1, floor(B*s')) (product in fp32) of the sigmoid-normalised score s' in [0,1].
+ * s_norm fp32 [M], label uint8 [M] (0 / non-zero), c_pos / c_neg int64 [B] are OVERWRITTEN.
+ * 1 <= B <= ARROL_MAX_BINS.  M == 0 zeroes the counts.
+ */
+int arrol_histogram(const float* s_norm, const uint8_t* label, int64_t M, int32_t B,
+                    int64_t* c_pos, int64_t* c_neg, void* stream);
+
+typedef struct arrol_policy {
+    float kappa;   /* target keep rate                    (paper: 0.5) */
+    float rho;     /* target positive ratio               (paper: 0.5) */
+    float lambda;  /* strength of the balance correction  (paper: 0.5) */
+    float p_min;   /* clip range of the survival probability (not given in the paper) */
+    float p_max;
+    float alpha;   /* Laplace smoothing of the histograms    (not given in the paper) */
+} arrol_policy;
+
+/*
+ * App. A.4: Laplace-smoothed likelihoods P(b|Y) = (c_b + alpha) / (sum c + alpha*B), prior pi = N+/(N+ + N-)
+ * (1/2 for empty buffers), Bayes posterior q(b) = pi P(b|1) / (pi P(b|1) + (1-pi) P(b|0)); Eq. 2:
+ * p(b) = clip(kappa + delta + lambda (rho - q(b)), p_min, p_max), with delta found by 64 bisection steps on
+ * [p_min - kappa - lambda, p_max - kappa + lambda] so that sum_b w_b p(b) = kappa, w_b = (c_b^+ + c_b^-)/total
+ * (the buffer distribution; uniform for empty buffers).  Computed in fp64.
+ * q_lut, p_lut fp32 [B]; delta NULL or a device double.  Policy fields must satisfy 0 <= kappa, rho <= 1,
+ * lambda >= 0, 0 <= p_min <= p_max <= 1, alpha >= 0.
+ */
+int arrol_calibrate(const int64_t* c_pos, const int64_t* c_neg, int32_t B, arrol_policy pol,
+                    float* q_lut, float* p_lut, double* delta, void* stream);
+
+/*
+ * Alg. 1 "Prune r_i w.p. 1 - p_i; record prune flag": p_i = p_lut[b(s_i)], rollout i survives iff
+ * uniforms[i] < p_i (fp32 comparison; the caller supplies the random numbers).
+ * s_norm, uniforms fp32 [N]; p_lut fp32 [B]; p_out NULL or fp32 [N]; keep_mask uint8 [N];
+ * survivor_idx int32 [N]: the survivors' ids ascending, then -1 up to N (so it can be handed to
+ * arrol_compact with n_keep = N: entries -1 yield empty destination rollouts); n_survivors device int32.
+ */
+int arrol_prune_bernoulli(const float* s_norm, const float* uniforms, int32_t N, const float* p_lut,
+                          int32_t B, float* p_out, uint8_t* keep_mask, int32_t* survivor_idx,
+                          int32_t* n_survivors, void* stream);
 
 /*
  * Benchmarking knob, not a stage of the method.  key "logprob_splits": number of vocabulary

@@ -29,6 +29,13 @@ class KVLayout(ctypes.Structure):
                 ("n_pages", ctypes.c_int64)]
 
 
+class Policy(ctypes.Structure):
+    """Parameters of the stochastic pruning policy (App. A.4 Eq. 2): keep rate, target ratio, correction
+    strength, clip range, Laplace smoothing."""
+    _fields_ = [("kappa", ctypes.c_float), ("rho", ctypes.c_float), ("lam", ctypes.c_float),
+                ("p_min", ctypes.c_float), ("p_max", ctypes.c_float), ("alpha", ctypes.c_float)]
+
+
 _lib = None
 
 _vp, _i32, _i64, _f32, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
@@ -44,6 +51,9 @@ _SIGNATURES = {
     "arrol_logprob_workspace_bytes": (_sz, [_i64, _i32, _i32]),
     "arrol_logprob": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
     "arrol_weighted_vote": (ctypes.c_int, [_vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp]),
+    "arrol_histogram": (ctypes.c_int, [_vp, _vp, _i64, _i32, _vp, _vp, _vp]),
+    "arrol_calibrate": (ctypes.c_int, [_vp, _vp, _i32, Policy, _vp, _vp, _vp, _vp]),
+    "arrol_prune_bernoulli": (ctypes.c_int, [_vp, _vp, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _vp]),
 }
 
 
@@ -221,3 +231,44 @@ def arrol_weighted_vote(prob, answer_id, n_questions, C, n_answers, want_tally=F
                                    _ptr(tally, torch.int64, "tally"), _stream(stream))
     _check("arrol_weighted_vote", rc)
     return (winner, tally) if want_tally else winner
+
+
+def arrol_histogram(s_norm, label, B, stream=None):
+    """s_norm fp32 [M] in [0,1], label uint8 [M] -> (c_pos, c_neg) int64 [B]."""
+    dev = s_norm.device
+    c_pos = torch.empty(B, dtype=torch.int64, device=dev)
+    c_neg = torch.empty(B, dtype=torch.int64, device=dev)
+    rc = lib().arrol_histogram(_ptr(s_norm, torch.float32, "s_norm"), _ptr(label, torch.uint8, "label"),
+                               s_norm.numel(), B, c_pos.data_ptr(), c_neg.data_ptr(), _stream(stream))
+    _check("arrol_histogram", rc)
+    return c_pos, c_neg
+
+
+def arrol_calibrate(c_pos, c_neg, policy, stream=None):
+    """int64 histograms [B] + Policy -> (q_lut fp32 [B], p_lut fp32 [B], delta fp64 device scalar)."""
+    B = c_pos.numel()
+    dev = c_pos.device
+    q_lut = torch.empty(B, dtype=torch.float32, device=dev)
+    p_lut = torch.empty(B, dtype=torch.float32, device=dev)
+    delta = torch.empty(1, dtype=torch.float64, device=dev)
+    rc = lib().arrol_calibrate(_ptr(c_pos, torch.int64, "c_pos"), _ptr(c_neg, torch.int64, "c_neg"), B, policy,
+                               q_lut.data_ptr(), p_lut.data_ptr(), delta.data_ptr(), _stream(stream))
+    _check("arrol_calibrate", rc)
+    return q_lut, p_lut, delta
+
+
+def arrol_prune_bernoulli(s_norm, uniforms, p_lut, want_p=False, stream=None):
+    """s_norm, uniforms fp32 [N], p_lut fp32 [B] -> dict(keep_mask, survivor_idx (padded with -1),
+    n_survivors (device int32), p (optional))."""
+    N = s_norm.numel()
+    dev = s_norm.device
+    out = dict(keep_mask=torch.empty(N, dtype=torch.uint8, device=dev),
+               survivor_idx=torch.empty(N, dtype=torch.int32, device=dev),
+               n_survivors=torch.empty(1, dtype=torch.int32, device=dev),
+               p=torch.empty(N, dtype=torch.float32, device=dev) if want_p else None)
+    rc = lib().arrol_prune_bernoulli(_ptr(s_norm, torch.float32, "s_norm"), _ptr(uniforms, torch.float32, "uniforms"),
+                                     N, _ptr(p_lut, torch.float32, "p_lut"), p_lut.numel(),
+                                     _ptr(out["p"], torch.float32, "p_out"), out["keep_mask"].data_ptr(),
+                                     out["survivor_idx"].data_ptr(), out["n_survivors"].data_ptr(), _stream(stream))
+    _check("arrol_prune_bernoulli", rc)
+    return out

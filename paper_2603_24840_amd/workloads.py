@@ -147,3 +147,18 @@ def vote_inputs(cfg, device):
     hidden = randn_bf16((n, cfg.d), g, device)
     answer_id = torch.randint(0, cfg.vote_a, (n,), generator=g, device=device, dtype=torch.int32)
     return hidden, answer_id
+
+
+def policy_inputs(cfg, device, buffer_len=4096, n_bins=128):
+    """Labelled score buffer for the stochastic policy: head scores ~ N(+0.8, 1) for rollouts that turned
+    out correct and N(-0.8, 1) for the others (a head of about 80 % accuracy, as the paper reports),
+    positives with probability 0.4, squashed by the sigmoid; plus the batch's own normalised scores and
+    uniforms for the Bernoulli draws."""
+    g = _gen(cfg, 7, device)
+    label = (torch.rand(buffer_len, generator=g, device=device) < 0.4)
+    raw = torch.randn(buffer_len, generator=g, device=device) + torch.where(label, 0.8, -0.8)
+    s_buf = torch.sigmoid(raw).to(torch.float32)
+    blabel = (torch.rand(cfg.n_rollouts, generator=g, device=device) < 0.4)
+    s_batch = torch.sigmoid(torch.randn(cfg.n_rollouts, generator=g, device=device) + torch.where(blabel, 0.8, -0.8))
+    uniforms = torch.rand(cfg.n_rollouts, generator=g, device=device, dtype=torch.float32)
+    return s_buf, label.to(torch.uint8), s_batch.to(torch.float32), uniforms

@@ -28,7 +28,8 @@ def test_header_declares_the_five_stage_calls():
     names = declared_functions()
     for fn in ["arrol_score", "arrol_select", "arrol_compact", "arrol_logprob", "arrol_weighted_vote",
                "arrol_compact_workspace_bytes", "arrol_logprob_workspace_bytes", "arrol_version",
-               "arrol_error_string", "arrol_set_tuning"]:
+               "arrol_error_string", "arrol_set_tuning", "arrol_histogram", "arrol_calibrate",
+               "arrol_prune_bernoulli"]:
         assert fn in names
 
 
@@ -95,6 +96,19 @@ def test_bad_arguments_are_rejected_on_the_host(pkg):
     assert L.arrol_compact(fake, lay, far, lay, *args, None, 0, None) == -2
     assert L.arrol_compact(fake, lay, far, lay, *args, fake, 4, None) == -2
     assert L.arrol_set_tuning(b"no_such_knob", 1) == -1
+    # stochastic policy: bin count out of range, null outputs, policy outside its domain
+    assert L.arrol_histogram(fake, fake, 10, 0, fake, fake, None) == -1
+    assert L.arrol_histogram(fake, fake, 10, 4096, fake, fake, None) == -1
+    assert L.arrol_histogram(None, fake, 10, 128, fake, fake, None) == -1
+    good = pkg.Policy(0.5, 0.5, 0.5, 0.05, 0.95, 1.0)
+    assert L.arrol_calibrate(fake, fake, 128, pkg.Policy(1.5, 0.5, 0.5, 0.05, 0.95, 1.0), fake, fake, None, None) == -1
+    assert L.arrol_calibrate(fake, fake, 128, pkg.Policy(0.5, 0.5, 0.5, 0.9, 0.1, 1.0), fake, fake, None, None) == -1
+    assert L.arrol_calibrate(fake, fake, 128, pkg.Policy(0.5, 0.5, -1.0, 0.05, 0.95, 1.0), fake, fake, None, None) == -1
+    assert L.arrol_calibrate(fake, fake, 0, good, fake, fake, None, None) == -1
+    assert L.arrol_calibrate(None, fake, 128, good, fake, fake, None, None) == -1
+    assert L.arrol_prune_bernoulli(fake, fake, -1, fake, 128, None, fake, fake, fake, None) == -1
+    assert L.arrol_prune_bernoulli(fake, fake, 8, fake, 128, None, fake, fake, None, None) == -1
+    assert L.arrol_prune_bernoulli(None, fake, 8, fake, 128, None, fake, fake, fake, None) == -1
 
 
 def test_binding_refuses_cpu_tensors(pkg):
