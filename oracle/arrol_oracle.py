@@ -347,3 +347,49 @@ def prune_bernoulli(s_norm_f32, uniforms_f32, p_lut_f32):
             keep[i] = 1
             surv.append(i)
     return p, keep, np.asarray(surv, dtype=np.int32), len(surv)
+
+
+# ----------------------------------------------------------------------------
+# in-place compaction ("hole filling") of the paged KV pool
+# ----------------------------------------------------------------------------
+def compact_inplace(kv, block_table_src, seq_len_src, survivor_idx):
+    """Sec. 4.3 (i): pruned requests leave the pool at once so that the freed capacity can be re-used.
+    The paper fixes no mechanism; this build's in-place contract: after the call the survivors' pages
+    occupy the dense prefix [0, n_live) of the SAME pool, moving as few pages as possible:
+      live   = set of physical pages referenced by the survivors (first ceil(seq_len/page_tokens) entries)
+      holes  = pages < n_live that are not live, ascending;  movers = live pages >= n_live, ascending
+      page movers[k] is copied (every layer, K and V) onto holes[k]; all other pages are untouched.
+    kv is modified in place.  Returns dict(block_table_dst [N_k, ppr] with -1 padding, seq_len_dst,
+    src_of_dst, n_pages_used = n_live, n_moved)."""
+    L, two, P, page_tokens, H, hd = kv.shape
+    ppr = block_table_src.shape[1]
+    n_keep = len(survivor_idx)
+    live = set()
+    pages_of = []
+    for r in range(n_keep):
+        s = int(survivor_idx[r])
+        n_pages = -(-int(seq_len_src[s]) // page_tokens) if s >= 0 else 0
+        row = [int(block_table_src[s, p]) for p in range(n_pages)]
+        pages_of.append(row)
+        live.update(row)
+    n_live = len(live)
+    holes = [p for p in range(n_live) if p not in live]
+    movers = sorted(p for p in live if p >= n_live)
+    assert len(holes) == len(movers)
+    new_page = {p: p for p in live}
+    for hole, mover in zip(holes, movers):
+        kv[:, :, hole] = kv[:, :, mover]
+        new_page[mover] = hole
+    bt_dst = np.full((n_keep, ppr), -1, dtype=np.int32)
+    sl_dst = np.zeros(n_keep, dtype=np.int32)
+    src_of_dst = np.full(n_keep, -1, dtype=np.int32)
+    for r in range(n_keep):
+        s = int(survivor_idx[r])
+        if s < 0:
+            continue
+        for p, page in enumerate(pages_of[r]):
+            bt_dst[r, p] = new_page[page]
+        sl_dst[r] = seq_len_src[s]
+        src_of_dst[r] = s
+    return dict(block_table_dst=bt_dst, seq_len_dst=sl_dst, src_of_dst=src_of_dst,
+                n_pages_used=n_live, n_moved=len(movers))

@@ -6,8 +6,9 @@
 
 namespace {
 
-constexpr int kScoreThreads = 256;
+constexpr int kScoreThreads = 512;
 constexpr int kScoreWaves = kScoreThreads / ARROL_WAVE;
+constexpr int kScoreUnroll = 4;          // 16-byte loads per lane in flight
 constexpr int kScoreLdsFloats = 16384;  // weights up to d = 16384 live in LDS (64 KiB)
 
 template <bool W_IN_LDS>
@@ -27,15 +28,15 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(
         const int64_t src_row = row_index ? row_index[row] : row;
         const u32x4* p = hidden + src_row * row_stride_vec;
         float acc0 = 0.f, acc1 = 0.f;
-        for (int v0 = 0; v0 < d_vec; v0 += 4 * ARROL_WAVE) {
-            u32x4 x[4];
+        for (int v0 = 0; v0 < d_vec; v0 += kScoreUnroll * ARROL_WAVE) {
+            u32x4 x[kScoreUnroll];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < kScoreUnroll; ++u) {
                 const int v = v0 + u * ARROL_WAVE + lane;
                 x[u] = v < d_vec ? __builtin_nontemporal_load(p + v) : u32x4{0u, 0u, 0u, 0u};
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < kScoreUnroll; ++u) {
                 const int v = v0 + u * ARROL_WAVE + lane;
                 if (v < d_vec) {
                     float4 wa, wb;

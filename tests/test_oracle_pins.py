@@ -547,3 +547,50 @@ def test_prune_bernoulli_decisions_and_rate():
     _, keep0, _, n0 = O.prune_bernoulli(s, np.zeros(2000, np.float32), p_lut)
     _, keep1, _, n1 = O.prune_bernoulli(s, np.ones(2000, np.float32), p_lut)
     assert n0 == 2000 and n1 == 0
+
+
+# ----------------------------------------------------------------------------- in-place compaction
+def test_compact_inplace_dense_prefix_content_and_minimal_moves():
+    rng = np.random.default_rng(61)
+    for trial in range(20):
+        N, ppr, pt = 9, 4, 4
+        seq = rng.integers(1, ppr * pt + 1, size=N).astype(np.int32)
+        kv, bt, seq, tok = make_paged(rng, N, ppr, pt, seq_lens=seq, extra_pages=int(rng.integers(0, 6)))
+        surv = np.sort(rng.choice(N, size=int(rng.integers(1, N + 1)), replace=False)).astype(np.int32)
+        before = kv.copy()
+        out = O.compact_inplace(kv, bt, seq, surv)
+        n_live = out["n_pages_used"]
+        used = []
+        for r, s in enumerate(surv):
+            n_pages = -(-int(seq[s]) // pt)
+            row = out["block_table_dst"][r]
+            assert np.all(row[n_pages:] == -1) and np.all(row[:n_pages] >= 0) and np.all(row[:n_pages] < n_live)
+            used.extend(row[:n_pages].tolist())
+            for t in range(int(seq[s])):                     # every token reads the same bytes as before
+                p, o = divmod(t, pt)
+                assert np.array_equal(kv[:, :, row[p], o], before[:, :, bt[s, p], o])
+            assert out["seq_len_dst"][r] == seq[s] and out["src_of_dst"][r] == s
+        assert sorted(used) == list(range(n_live))           # the prefix is dense and nothing is shared
+        # minimality: a page must move iff it is live and lies outside the prefix; everything else is untouched
+        live_before = set(int(bt[s, p]) for s in surv for p in range(-(-int(seq[s]) // pt)))
+        must_move = [p for p in live_before if p >= n_live]
+        assert out["n_moved"] == len(must_move)
+        changed = [p for p in range(kv.shape[2]) if not np.array_equal(kv[:, :, p], before[:, :, p])]
+        assert len(changed) <= out["n_moved"] and all(p < n_live and p not in live_before for p in changed)
+
+
+def test_compact_inplace_identity_and_pairing_order():
+    rng = np.random.default_rng(62)
+    N, ppr, pt = 4, 2, 2
+    kv, _, seq, _ = make_paged(rng, N, ppr, pt, extra_pages=0)
+    dense = np.arange(N * ppr, dtype=np.int32).reshape(N, ppr)
+    before = kv.copy()
+    out = O.compact_inplace(kv, dense, seq, np.array([0, 1], np.int32))     # survivors already form the prefix
+    assert out["n_moved"] == 0 and np.array_equal(kv, before) and np.array_equal(out["block_table_dst"], dense[:2])
+    # survivors 2,3 own pages 4..7: holes 0..3 are filled in ascending order by movers 4..7
+    out = O.compact_inplace(kv, dense, seq, np.array([2, 3], np.int32))
+    assert out["n_moved"] == 4 and out["block_table_dst"].tolist() == [[0, 1], [2, 3]]
+    assert np.array_equal(kv[:, :, 0:4], before[:, :, 4:8])
+    # an empty survivor set frees everything
+    out = O.compact_inplace(kv, dense, seq, np.array([], np.int32))
+    assert out["n_pages_used"] == 0 and out["n_moved"] == 0
