@@ -116,6 +116,29 @@ int arrol_compact(const void* kv_src, arrol_kv_layout src, void* kv_dst, arrol_k
                   void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Stage 3, in-place variant ("hole filling").  Same paper passage: pruned requests leave the pool so that
+ * the freed capacity is re-used (Sec. 4.3 (i)); no second pool is needed and only the pages that lie in the
+ * wrong place move.  With live = the set of physical pages the survivors reference (first
+ * ceil(seq_len/page_tokens) table entries each) and n_live its size: holes = pages < n_live that are not
+ * live, movers = live pages >= n_live, both ascending; page movers[k] is copied (every layer, K and V) onto
+ * page holes[k], all other pages stay untouched.  Afterwards the survivors occupy exactly pages
+ * [0, n_live) of the SAME pool and [n_live, n_pages) is free.
+ *   block_table_dst[r][p] = final page of survivor rank r's logical page p, -1 beyond its length;
+ *   seq_len_dst[r], src_of_dst[r] as in arrol_compact; *n_pages_used = n_live; *n_moved (NULL allowed) =
+ *   number of pages copied.
+ * A survivor id outside [0, n_src) is an empty rollout; table entries outside [0, n_pages) are ignored
+ * (reported as -1).  Token buffers are not touched (they are indexed by rollout, not by page).
+ * workspace: arrol_compact_inplace_workspace_bytes(layout.n_pages) bytes, 16-byte aligned.
+ */
+size_t arrol_compact_inplace_workspace_bytes(int64_t n_pages);
+int arrol_compact_inplace(void* kv, arrol_kv_layout layout, const int32_t* block_table_src,
+                          const int32_t* seq_len_src, int32_t max_pages_per_seq,
+                          const int32_t* survivor_idx, int32_t n_src, int32_t n_keep,
+                          int32_t* block_table_dst, int32_t* seq_len_dst, int32_t* src_of_dst,
+                          int64_t* n_pages_used, int64_t* n_moved, void* workspace,
+                          size_t workspace_bytes, void* stream);
+
+/*
  * Stage 4 -- per-token log-probability of the sampled token (the policy term of GRPO's
  * importance ratio, Sec. 3; computed on the re-batched survivors, Sec. 4.3 (ii), Alg. 1):
  *   z_t = W h_t,  logprob_t = z_t[y_t] - logsumexp_v z_t[v]      (temperature 1, no bias)

@@ -48,6 +48,9 @@ _SIGNATURES = {
     "arrol_compact_workspace_bytes": (_sz, [_i32]),
     "arrol_compact": (ctypes.c_int, [_vp, KVLayout, _vp, KVLayout, _vp, _vp, _i32, _vp, _i32, _vp, _i32, _i32,
                                      _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "arrol_compact_inplace_workspace_bytes": (_sz, [_i64]),
+    "arrol_compact_inplace": (ctypes.c_int, [_vp, KVLayout, _vp, _vp, _i32, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp,
+                                             _vp, _sz, _vp]),
     "arrol_logprob_workspace_bytes": (_sz, [_i64, _i32, _i32]),
     "arrol_logprob": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
     "arrol_weighted_vote": (ctypes.c_int, [_vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp]),
@@ -189,6 +192,31 @@ def arrol_compact(kv_src, kv_dst, block_table_src, seq_len_src, tokens_src, surv
         _ptr(out["n_pages_used"], torch.int64, "n_pages_used"),
         _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
     _check("arrol_compact", rc)
+    return out
+
+
+def arrol_compact_inplace(kv, block_table_src, seq_len_src, survivor_idx, workspace=None, stream=None):
+    """Moves the survivors' pages into the dense prefix of the SAME pool (kv is modified in place).
+    Returns dict(block_table_dst, seq_len_dst, src_of_dst, n_pages_used, n_moved)."""
+    dev = kv.device
+    n_src, ppr = block_table_src.shape
+    n_keep = survivor_idx.numel()
+    out = dict(block_table_dst=torch.empty((n_keep, ppr), dtype=torch.int32, device=dev),
+               seq_len_dst=torch.empty(n_keep, dtype=torch.int32, device=dev),
+               src_of_dst=torch.empty(n_keep, dtype=torch.int32, device=dev),
+               n_pages_used=torch.empty(1, dtype=torch.int64, device=dev),
+               n_moved=torch.empty(1, dtype=torch.int64, device=dev))
+    lay = kv_layout_of(kv)
+    need = lib().arrol_compact_inplace_workspace_bytes(lay.n_pages)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+    rc = lib().arrol_compact_inplace(
+        _ptr(kv, torch.bfloat16, "kv"), lay, _ptr(block_table_src, torch.int32, "block_table_src"),
+        _ptr(seq_len_src, torch.int32, "seq_len_src"), ppr, _ptr(survivor_idx, torch.int32, "survivor_idx"),
+        n_src, n_keep, out["block_table_dst"].data_ptr(), out["seq_len_dst"].data_ptr(),
+        out["src_of_dst"].data_ptr(), out["n_pages_used"].data_ptr(), out["n_moved"].data_ptr(),
+        _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
+    _check("arrol_compact_inplace", rc)
     return out
 
 

@@ -121,6 +121,129 @@ __global__ __launch_bounds__(kCopyThreads) void compact_copy_kernel(
 
 __global__ void compact_empty_kernel(int64_t* n_pages_used) { *n_pages_used = 0; }
 
+// ---- in-place variant: fill the holes below the live-page count with the live pages above it ----------
+// workspace layout (int32): live[P] | new_page[P] | hole_list[P] | mover_list[P] | counters[2] = {n_live, m}
+
+__global__ void inplace_clear_kernel(int32_t* live, int64_t P) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < P) live[i] = 0;
+}
+
+// one thread per (survivor rank, logical page): flag the physical page as live; thread p == 0 writes the
+// per-survivor outputs
+__global__ void inplace_mark_kernel(const int32_t* __restrict__ survivor_idx, const int32_t* __restrict__ seq_len_src,
+                                    const int32_t* __restrict__ block_table_src, int n_src, int n_keep,
+                                    int page_tokens, int ppr, int64_t P, int32_t* __restrict__ live,
+                                    int32_t* __restrict__ seq_len_dst, int32_t* __restrict__ src_of_dst) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i >= static_cast<int64_t>(n_keep) * ppr) return;
+    const int r = static_cast<int>(i / ppr), p = static_cast<int>(i % ppr);
+    const int src = survivor_idx[r];
+    const bool valid = src >= 0 && src < n_src;
+    if (p == 0) {
+        seq_len_dst[r] = valid ? seq_len_src[src] : 0;
+        src_of_dst[r] = valid ? src : -1;
+    }
+    if (p < pages_of(seq_len_src, src, n_src, page_tokens, ppr)) {
+        const int64_t page = block_table_src[static_cast<int64_t>(src) * ppr + p];
+        if (page >= 0 && page < P) live[page] = 1;
+    }
+}
+
+// one workgroup: n_live = number of live pages; holes = dead pages below n_live, movers = live pages at or
+// above it, both ascending (ballot + popcount ranks, LDS carries); new_page[] maps every live page to its
+// final position
+__global__ __launch_bounds__(kPlanThreads) void inplace_plan_kernel(
+    const int32_t* __restrict__ live, int64_t P, int32_t* __restrict__ new_page, int32_t* __restrict__ hole_list,
+    int32_t* __restrict__ mover_list, int32_t* __restrict__ counters, int64_t* __restrict__ n_pages_used,
+    int64_t* __restrict__ n_moved) {
+    __shared__ int wave_h[kPlanThreads / ARROL_WAVE], wave_m[kPlanThreads / ARROL_WAVE];
+    __shared__ int carry_h, carry_m, total_s;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int cnt = 0;
+    for (int64_t p = tid; p < P; p += kPlanThreads) cnt += live[p];
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) cnt += __shfl_xor(cnt, m, ARROL_WAVE);
+    if (lane == 0) wave_h[wave] = cnt;
+    if (tid == 0) { carry_h = 0; carry_m = 0; }
+    __syncthreads();
+    if (tid == 0) {
+        int t = 0;
+        for (int w = 0; w < kPlanThreads / ARROL_WAVE; ++w) t += wave_h[w];
+        total_s = t;
+    }
+    __syncthreads();
+    const int64_t n_live = total_s;
+    for (int64_t p0 = 0; p0 < P; p0 += kPlanThreads) {
+        const int64_t p = p0 + tid;
+        const bool is_live = p < P && live[p] != 0;
+        const bool hole = p < n_live && !is_live;
+        const bool mover = p < P && p >= n_live && is_live;
+        const uint64_t bh = __ballot(hole), bm = __ballot(mover);
+        __syncthreads();   // previous chunk's carries have been read
+        if (lane == 0) { wave_h[wave] = __popcll(bh); wave_m[wave] = __popcll(bm); }
+        __syncthreads();
+        int before_h = carry_h, before_m = carry_m;
+        for (int w = 0; w < wave; ++w) { before_h += wave_h[w]; before_m += wave_m[w]; }
+        const uint64_t below = (1ull << lane) - 1ull;
+        if (hole) hole_list[before_h + __popcll(bh & below)] = static_cast<int32_t>(p);
+        if (mover) mover_list[before_m + __popcll(bm & below)] = static_cast<int32_t>(p);
+        if (p < P) new_page[p] = (is_live && p < n_live) ? static_cast<int32_t>(p) : -1;
+        __syncthreads();
+        if (tid == kPlanThreads - 1) { carry_h = before_h + __popcll(bh); carry_m = before_m + __popcll(bm); }
+    }
+    __syncthreads();
+    const int m = carry_m;   // == carry_h: as many holes as movers
+    for (int k = tid; k < m; k += kPlanThreads) new_page[mover_list[k]] = hole_list[k];
+    if (tid == 0) {
+        counters[0] = static_cast<int32_t>(n_live);
+        counters[1] = m;
+        *n_pages_used = n_live;
+        if (n_moved) *n_moved = m;
+    }
+}
+
+// copy blocks: (slab, k) moves page mover_list[k] onto hole_list[k]; table blocks: remapped block tables
+__global__ __launch_bounds__(kCopyThreads) void inplace_copy_kernel(
+    u32x4* __restrict__ kv, int64_t chunk_vec, int64_t P, const int32_t* __restrict__ hole_list,
+    const int32_t* __restrict__ mover_list, const int32_t* __restrict__ counters, int64_t m_bound, int64_t kv_blocks,
+    const int32_t* __restrict__ new_page, const int32_t* __restrict__ survivor_idx,
+    const int32_t* __restrict__ seq_len_src, const int32_t* __restrict__ block_table_src, int n_src, int page_tokens,
+    int ppr, int32_t* __restrict__ block_table_dst) {
+    const int64_t bid = blockIdx.x;
+    if (bid < kv_blocks) {
+        const int64_t slab = bid / m_bound, k = bid - slab * m_bound;
+        if (k >= counters[1]) return;
+        const u32x4* s = kv + (slab * P + mover_list[k]) * chunk_vec;
+        u32x4* d = kv + (slab * P + hole_list[k]) * chunk_vec;
+        for (int64_t v0 = 0; v0 < chunk_vec; v0 += kCopyThreads * kCopyUnroll) {
+            u32x4 x[kCopyUnroll];
+#pragma unroll
+            for (int u = 0; u < kCopyUnroll; ++u) {
+                const int64_t v = v0 + u * kCopyThreads + threadIdx.x;
+                if (v < chunk_vec) x[u] = __builtin_nontemporal_load(s + v);
+            }
+#pragma unroll
+            for (int u = 0; u < kCopyUnroll; ++u) {
+                const int64_t v = v0 + u * kCopyThreads + threadIdx.x;
+                if (v < chunk_vec) __builtin_nontemporal_store(x[u], d + v);
+            }
+        }
+    } else {
+        const int r = static_cast<int>(bid - kv_blocks);
+        const int src = survivor_idx[r];
+        const int np = pages_of(seq_len_src, src, n_src, page_tokens, ppr);
+        for (int p = threadIdx.x; p < ppr; p += kCopyThreads) {
+            int32_t out = -1;
+            if (p < np) {
+                const int64_t page = block_table_src[static_cast<int64_t>(src) * ppr + p];
+                if (page >= 0 && page < P) out = new_page[page];
+            }
+            block_table_dst[static_cast<int64_t>(r) * ppr + p] = out;
+        }
+    }
+}
+
 bool same_geometry(const arrol_kv_layout& a, const arrol_kv_layout& b) {
     return a.n_layers == b.n_layers && a.page_tokens == b.page_tokens && a.n_kv_heads == b.n_kv_heads &&
            a.head_dim == b.head_dim;
@@ -177,5 +300,62 @@ extern "C" int arrol_compact(const void* kv_src, arrol_kv_layout src, void* kv_d
                        static_cast<const u32x4*>(kv_src), static_cast<u32x4*>(kv_dst), chunk_bytes / 16,
                        src.n_pages, dst.n_pages, block_table_src, survivor_idx, base, n_src, n_keep,
                        max_pages_per_seq, kv_blocks, tokens_src, tokens_dst, max_len);
+    return arrol_launch_status();
+}
+
+extern "C" size_t arrol_compact_inplace_workspace_bytes(int64_t n_pages) {
+    if (n_pages < 0) return 0;
+    return ((4 * static_cast<size_t>(n_pages) + 2) * sizeof(int32_t) + 255) & ~static_cast<size_t>(255);
+}
+
+extern "C" int arrol_compact_inplace(void* kv, arrol_kv_layout layout, const int32_t* block_table_src,
+                                     const int32_t* seq_len_src, int32_t max_pages_per_seq,
+                                     const int32_t* survivor_idx, int32_t n_src, int32_t n_keep,
+                                     int32_t* block_table_dst, int32_t* seq_len_dst, int32_t* src_of_dst,
+                                     int64_t* n_pages_used, int64_t* n_moved, void* workspace,
+                                     size_t workspace_bytes, void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (n_keep < 0 || n_src < 0 || !n_pages_used) return ARROL_EINVAL;
+    if (layout.n_layers < 1 || layout.page_tokens < 1 || layout.n_kv_heads < 1 || layout.head_dim < 1 ||
+        layout.n_pages < 0 || layout.n_pages > INT32_MAX || max_pages_per_seq < 1)
+        return ARROL_EINVAL;
+    const int64_t chunk_bytes = static_cast<int64_t>(layout.page_tokens) * layout.n_kv_heads * layout.head_dim * 2;
+    if (chunk_bytes % 16) return ARROL_EINVAL;
+    if (n_keep > 0 && (!kv || !block_table_src || !seq_len_src || !survivor_idx || !block_table_dst || !seq_len_dst ||
+                       !src_of_dst || !arrol_aligned16(kv)))
+        return ARROL_EINVAL;
+    if (!workspace || !arrol_aligned16(workspace) ||
+        workspace_bytes < arrol_compact_inplace_workspace_bytes(layout.n_pages))
+        return ARROL_EWORKSPACE;
+    const int64_t P = layout.n_pages;
+    const int64_t slots = static_cast<int64_t>(n_keep) * max_pages_per_seq;
+    if (slots > INT32_MAX) return ARROL_EINVAL;
+    int32_t* live = static_cast<int32_t*>(workspace);
+    int32_t* new_page = live + P;
+    int32_t* hole_list = new_page + P;
+    int32_t* mover_list = hole_list + P;
+    int32_t* counters = mover_list + P;
+    if (P > 0) {
+        hipLaunchKernelGGL(inplace_clear_kernel, dim3(static_cast<unsigned>((P + 255) / 256)), dim3(256), 0, st, live, P);
+        if (hipGetLastError() != hipSuccess) return ARROL_EHIP;
+    }
+    if (slots > 0) {
+        hipLaunchKernelGGL(inplace_mark_kernel, dim3(static_cast<unsigned>((slots + 255) / 256)), dim3(256), 0, st,
+                           survivor_idx, seq_len_src, block_table_src, n_src, n_keep, layout.page_tokens,
+                           max_pages_per_seq, P, live, seq_len_dst, src_of_dst);
+        if (hipGetLastError() != hipSuccess) return ARROL_EHIP;
+    }
+    hipLaunchKernelGGL(inplace_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, live, P, new_page, hole_list,
+                       mover_list, counters, n_pages_used, n_moved);
+    if (hipGetLastError() != hipSuccess) return ARROL_EHIP;
+    const int64_t m_bound = slots < P ? slots : P;   // no more movers than survivor pages or pool pages
+    const int64_t kv_blocks = m_bound * layout.n_layers * 2;
+    const int64_t blocks = kv_blocks + n_keep;
+    if (blocks > INT32_MAX) return ARROL_EINVAL;
+    if (blocks == 0) return ARROL_OK;
+    hipLaunchKernelGGL(inplace_copy_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kCopyThreads), 0, st,
+                       static_cast<u32x4*>(kv), chunk_bytes / 16, P, hole_list, mover_list, counters,
+                       m_bound > 0 ? m_bound : 1, kv_blocks, new_page, survivor_idx, seq_len_src, block_table_src,
+                       n_src, layout.page_tokens, max_pages_per_seq, block_table_dst);
     return arrol_launch_status();
 }

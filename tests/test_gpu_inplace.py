@@ -1,0 +1,101 @@
+"""Parity of the in-place (hole-filling) KV compaction with the oracle: bit-exact pool, tables and counts."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from helpers import bits, npy
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def A():
+    import paper_2603_24840_amd as pkg
+    pkg.lib()
+    return pkg
+
+
+@pytest.fixture(scope="module")
+def W():
+    from paper_2603_24840_amd import workloads
+    return workloads
+
+
+def run_case(A, kv, bt, sl, surv):
+    ref_kv = bits(kv).copy()
+    ref = O.compact_inplace(ref_kv, npy(bt), npy(sl), npy(surv))
+    out = A.arrol_compact_inplace(kv, bt, sl, surv)
+    torch.cuda.synchronize()
+    assert int(out["n_pages_used"][0]) == ref["n_pages_used"] and int(out["n_moved"][0]) == ref["n_moved"]
+    assert np.array_equal(npy(out["block_table_dst"]), ref["block_table_dst"])
+    assert np.array_equal(npy(out["seq_len_dst"]), ref["seq_len_dst"])
+    assert np.array_equal(npy(out["src_of_dst"]), ref["src_of_dst"])
+    assert np.array_equal(bits(kv), ref_kv)                      # the whole pool, moved and untouched pages alike
+    return out, ref
+
+
+def test_inplace_tiny_config(A, W):
+    cfg = W.CONFIGS["tiny"]
+    print("[case] inplace tiny", flush=True)
+    kv, bt, sl, _ = W.compact_inputs(cfg, DEV)
+    p = W.select_inputs(cfg, DEV)
+    _, surv = A.arrol_select(p, cfg.n_prompts, cfg.G, cfg.K, cfg.rho)
+    out, ref = run_case(A, kv, bt, sl, surv)
+    assert ref["n_pages_used"] == cfg.n_keep * cfg.pages_per_rollout and 0 < ref["n_moved"] < ref["n_pages_used"]
+
+
+@pytest.mark.parametrize("head_dim,pt,n_prompts,G,K,extra", [(64, 16, 6, 5, 2, 5), (128, 16, 40, 8, 4, 0), (8, 1, 3, 4, 1, 3),
+                                                          (40, 3, 9, 3, 3, 1), (64, 16, 300, 8, 4, 77)])
+def test_inplace_ragged(A, W, head_dim, pt, n_prompts, G, K, extra):
+    print("[case] inplace hd=%d page=%d prompts=%d G=%d K=%d" % (head_dim, pt, n_prompts, G, K), flush=True)
+    cfg = W.shrink(W.CONFIGS["tiny"], n_prompts=n_prompts, G=G, K=K, head_dim=head_dim, page_tokens=pt, ckpt_len=37,
+                   n_layers=2, n_kv_heads=2)
+    kv, bt, sl, _ = W.compact_inputs(cfg, DEV, extra_pages=extra, ragged=True)
+    g = torch.Generator(device="cpu"); g.manual_seed(n_prompts)
+    pick = torch.stack([torch.sort(torch.randperm(G, generator=g)[:K])[0] + i * G
+                        for i in range(n_prompts)]).reshape(-1).to(torch.int32).to(DEV)
+    run_case(A, kv, bt, sl, pick)
+
+
+def test_inplace_degenerate_cases(A, W):
+    cfg = W.CONFIGS["tiny"]
+    kv, bt, sl, _ = W.compact_inputs(cfg, DEV)
+    before = kv.clone()
+    # nobody survives: nothing moves, everything is free
+    out, _ = run_case(A, kv, bt, sl, torch.empty(0, dtype=torch.int32, device=DEV))
+    assert torch.equal(kv.view(torch.int16), before.view(torch.int16))
+    # everybody survives and the pool has no spare pages: already dense, nothing moves
+    out, ref = run_case(A, kv, bt, sl, torch.arange(cfg.n_rollouts, dtype=torch.int32, device=DEV))
+    assert ref["n_moved"] == 0 and torch.equal(kv.view(torch.int16), before.view(torch.int16))
+    # invalid survivor ids and out-of-range table entries are ignored
+    bt2 = bt.clone(); bt2[5, 1] = -3; bt2[5, 2] = kv.shape[2] + 9
+    surv = torch.tensor([5, -1, 9999, 7], dtype=torch.int32, device=DEV)
+    out = A.arrol_compact_inplace(kv, bt2, sl, surv)
+    torch.cuda.synchronize()
+    assert npy(out["src_of_dst"]).tolist() == [5, -1, -1, 7] and int(out["n_pages_used"][0]) == 6
+    row = npy(out["block_table_dst"])[0]
+    assert row[1] == -1 and row[2] == -1 and 0 <= row[0] < 6 and 0 <= row[3] < 6
+
+
+def test_inplace_llama1b_full_size(A, W):
+    cfg = W.CONFIGS["llama1b"]
+    print("[case] inplace llama1b full pool; oracle on 2 of 16 layers, content property on all", flush=True)
+    kv, bt, sl, _ = W.compact_inputs(cfg, DEV)
+    p = W.select_inputs(cfg, DEV)
+    _, surv = A.arrol_select(p, cfg.n_prompts, cfg.G, cfg.K, cfg.rho)
+    flat_old = bt[surv.long()].reshape(-1).long()
+    probe = kv[:, :, flat_old, 0, 0, :4].clone()                 # a fingerprint of every survivor page, all layers
+    host_before = {layer: bits(kv[layer:layer + 1]).copy() for layer in (0, cfg.n_layers - 1)}
+    out = A.arrol_compact_inplace(kv, bt, sl, surv)
+    torch.cuda.synchronize()
+    n_live = cfg.n_keep * cfg.pages_per_rollout
+    assert int(out["n_pages_used"][0]) == n_live
+    for layer, ref_kv in host_before.items():
+        ref = O.compact_inplace(ref_kv, npy(bt), npy(sl), npy(surv))
+        assert np.array_equal(bits(kv[layer:layer + 1]), ref_kv), layer
+    assert np.array_equal(npy(out["block_table_dst"]), ref["block_table_dst"]) and int(out["n_moved"][0]) == ref["n_moved"]
+    flat_new = out["block_table_dst"].reshape(-1).long()
+    assert int(flat_new.max()) == n_live - 1 and torch.unique(flat_new).numel() == n_live
+    assert torch.equal(kv[:, :, flat_new, 0, 0, :4].view(torch.int16), probe.view(torch.int16))
