@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=8192)
     ap.add_argument("--calibrate-copy", action="store_true")
+    ap.add_argument("--inplace-compaction", action="store_true",
+                    help="also time arrol_compact_inplace on the same pool and survivors (extra JSON object)")
     ap.add_argument("--tune", default="", help="comma list key=value passed to arrol_set_tuning (experiments)")
     ap.add_argument("--only", default="", help="comma list of stages to run (profiling aid); default all")
     return ap.parse_args()
@@ -249,6 +251,28 @@ def main():
         "logprob_tokens_per_s": T / lp_s if lp_s > 0 else 0.0,
         "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
     }
+    if args.inplace_compaction:
+        # the in-place variant rewrites the pool, so the pool is restored (untimed) before every call
+        orig = kv_src.clone()
+        iws = torch.empty(max(16, A.lib().arrol_compact_inplace_workspace_bytes(kv_src.shape[2])), dtype=torch.uint8, device=dev)
+        times = []
+        for _ in range(args.warmup + args.steps):
+            kv_src.copy_(orig)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            iout = A.arrol_compact_inplace(kv_src, block_table, seq_len, surv, workspace=iws)
+            e1.record()
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1))
+        kv_src.copy_(orig)
+        del orig
+        ms = sum(times[args.warmup:]) / args.steps
+        moved = int(iout["n_moved"][0])
+        moved_bytes = 2.0 * moved * cfg.n_layers * 2 * cfg.chunk_bytes
+        result["compact_inplace"] = {"ms": ms, "pages_live": int(iout["n_pages_used"][0]), "pages_moved": moved,
+                                     "bytes_read_plus_written": moved_bytes, "GBps": moved_bytes / ms / 1e6,
+                                     "frac_of_hbm_peak": moved_bytes / ms / 1e6 / HBM_PEAK_GBPS}
     if not args.skip_cpu_baseline and not only:
         tensors = dict(hidden=hidden, w=w, bias=bias, prob=prob, kv_src=kv_src, kv_dst=kv_dst,
                        block_table=block_table, seq_len=seq_len, tokens=tokens, lp_hidden=lp_hidden,
