@@ -393,3 +393,31 @@ def compact_inplace(kv, block_table_src, seq_len_src, survivor_idx):
         src_of_dst[r] = s
     return dict(block_table_dst=bt_dst, seq_len_dst=sl_dst, src_of_dst=src_of_dst,
                 n_pages_used=n_live, n_moved=len(movers))
+
+
+# ----------------------------------------------------------------------------
+# 2-layer MLP quality head
+# ----------------------------------------------------------------------------
+def score_mlp(hidden_bits, w1_bits, b1, w2, b2=0.0):
+    """Quality head as a 2-layer MLP (Sec. 4.2: the head "can be a simple 2-layer MLP") followed by the
+    sigmoid normalisation of App. A.4.  Reading (the paper gives neither width nor activation):
+        a = relu(W1 h + b1),  s = <w2, a> + b2,  q = sigmoid(s)
+    hidden_bits [N, d] uint16 (bf16), w1_bits [m, d] uint16 (bf16), b1 [m] fp32, w2 [m] fp32.
+    Returns (s, q) float64 [N]."""
+    h = bf16_bits_to_f64(hidden_bits)
+    W1 = bf16_bits_to_f64(w1_bits)
+    b1 = np.asarray(b1, dtype=np.float32).astype(np.float64)
+    w2 = np.asarray(w2, dtype=np.float32).astype(np.float64)
+    n = h.shape[0]
+    s = np.empty(n, dtype=np.float64)
+    q = np.empty(n, dtype=np.float64)
+    for i in range(n):
+        pre = W1 @ h[i] + b1
+        act = np.where(pre > 0.0, pre, 0.0)
+        s[i] = math.fsum(act * w2) + float(b2)
+        if s[i] >= 0.0:
+            q[i] = 1.0 / (1.0 + math.exp(-s[i]))
+        else:
+            e = math.exp(s[i])
+            q[i] = e / (1.0 + e)
+    return s, q

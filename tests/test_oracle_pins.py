@@ -594,3 +594,54 @@ def test_compact_inplace_identity_and_pairing_order():
     # an empty survivor set frees everything
     out = O.compact_inplace(kv, dense, seq, np.array([], np.int32))
     assert out["n_pages_used"] == 0 and out["n_moved"] == 0
+
+
+# ----------------------------------------------------------------------------- MLP head
+def test_score_mlp_reduces_to_the_linear_head_when_relu_is_inactive():
+    # one hidden unit with a bias large enough to keep it positive: s = w2 (w.h + b1) + b2
+    rng = np.random.default_rng(71)
+    d = 16
+    hb = f32_to_bf16_bits(rng.standard_normal((6, d)))
+    w = rng.standard_normal(d).astype(np.float32)
+    wb = f32_to_bf16_bits(w)[None, :]
+    s, q = O.score_mlp(hb, wb, np.array([64.0], np.float32), np.array([0.5], np.float32), -32.0)
+    w_rounded = O.bf16_bits_to_f64(wb[0]).astype(np.float32)
+    s_lin, q_lin = O.score(hb, w_rounded, 0.0)
+    assert np.allclose(s, 0.5 * s_lin, rtol=0, atol=1e-12) and np.allclose(q, 0.5 * (1 + np.tanh(0.25 * s_lin)), atol=1e-12)
+
+
+def test_score_mlp_dead_units_and_unit_permutation():
+    rng = np.random.default_rng(72)
+    d, m, N = 8, 12, 5
+    hb = f32_to_bf16_bits(rng.standard_normal((N, d)))
+    W1 = f32_to_bf16_bits(rng.standard_normal((m, d)))
+    b1 = rng.standard_normal(m).astype(np.float32)
+    w2 = rng.standard_normal(m).astype(np.float32)
+    s, q = O.score_mlp(hb, W1, b1, w2, 0.25)
+    # every unit switched off by a very negative bias: only b2 is left
+    s0, q0 = O.score_mlp(hb, W1, np.full(m, -1e6, np.float32), w2, 0.25)
+    assert np.all(s0 == 0.25) and np.allclose(q0, 1 / (1 + math.exp(-0.25)), atol=1e-15)
+    # hidden units are exchangeable
+    perm = rng.permutation(m)
+    s1, _ = O.score_mlp(hb, W1[perm], b1[perm], w2[perm], 0.25)
+    assert np.allclose(s1, s, rtol=0, atol=1e-12)
+    # s - b2 is linear in w2
+    s2, _ = O.score_mlp(hb, W1, b1, (2 * w2).astype(np.float32), 0.25)
+    assert np.allclose(s2 - 0.25, 2 * (s - 0.25), rtol=0, atol=1e-12)
+
+
+def test_score_mlp_exact_rational():
+    rng = np.random.default_rng(73)
+    d, m = 6, 4
+    hb = f32_to_bf16_bits(rng.standard_normal((3, d)))
+    W1 = f32_to_bf16_bits(rng.standard_normal((m, d)))
+    b1 = rng.standard_normal(m).astype(np.float32)
+    w2 = rng.standard_normal(m).astype(np.float32)
+    s, _ = O.score_mlp(hb, W1, b1, w2, -0.5)
+    for i in range(3):
+        tot = Fraction(-1, 2)
+        for u in range(m):
+            pre = sum(bits_to_fraction(W1[u, k]) * bits_to_fraction(hb[i, k]) for k in range(d)) + Fraction(float(b1[u]))
+            if pre > 0:
+                tot += pre * Fraction(float(w2[u]))
+        assert abs(s[i] - float(tot)) < 1e-13
