@@ -62,6 +62,18 @@ int arrol_score(const void* hidden, int64_t row_stride_elems, const int64_t* row
                 float* score_out, float* prob_out, void* stream);
 
 /*
+ * Stage 1, MLP head (Sec. 4.2: the quality head "can be a simple 2-layer MLP"; neither width nor
+ * activation is given - ReLU is this build's reading):
+ *   a = relu(W1 h + b1),  s_i = <w2, a> + b2,  q_i = sigmoid(s_i)
+ * hidden, row_stride_elems, row_index, score_out, prob_out as in arrol_score.
+ * w1 bf16 [m, d] row-major, 16-byte aligned; b1 NULL (zero) or fp32 [m]; w2 fp32 [m]; b2 by value; m >= 1.
+ * bf16 products accumulated in fp32 on the matrix cores; the [n_rows, m] activations are never stored.
+ */
+int arrol_score_mlp(const void* hidden, int64_t row_stride_elems, const int64_t* row_index,
+                    const void* w1, const float* b1, const float* w2, float b2, int32_t n_rows,
+                    int32_t d, int32_t m, float* score_out, float* prob_out, void* stream);
+
+/*
  * Stage 2 -- per-group keep-K selection by the balance rule (Thm 4.2 / App. A.1):
  * with live set A, mu_{-j} = mean of q_i over A \ {j}; prune argmin_j |mu_{-j} - rho|;
  * repeat on the shrunken group until K remain.  Decisions are taken on integers

@@ -44,6 +44,7 @@ _SIGNATURES = {
     "arrol_error_string": (ctypes.c_char_p, [ctypes.c_int]),
     "arrol_set_tuning": (ctypes.c_int, [ctypes.c_char_p, ctypes.c_int]),
     "arrol_score": (ctypes.c_int, [_vp, _i64, _vp, _vp, _f32, _i32, _i32, _vp, _vp, _vp]),
+    "arrol_score_mlp": (ctypes.c_int, [_vp, _i64, _vp, _vp, _vp, _vp, _f32, _i32, _i32, _i32, _vp, _vp, _vp]),
     "arrol_select": (ctypes.c_int, [_vp, _i32, _i32, _i32, _f32, _vp, _vp, _vp]),
     "arrol_compact_workspace_bytes": (_sz, [_i32]),
     "arrol_compact": (ctypes.c_int, [_vp, KVLayout, _vp, KVLayout, _vp, _vp, _i32, _vp, _i32, _vp, _i32, _i32,
@@ -132,6 +133,27 @@ def arrol_score(hidden, w, bias=0.0, row_index=None, out_score=None, out_prob=No
                            _stream(stream))
     _check("arrol_score", rc)
     return out_score, out_prob
+
+
+def arrol_score_mlp(hidden, w1, b1, w2, b2=0.0, row_index=None, stream=None):
+    """hidden bf16 [R, d], w1 bf16 [m, d], b1 fp32 [m] or None, w2 fp32 [m] -> (score, prob) fp32 [n]."""
+    if hidden.dim() != 2 or hidden.dtype != torch.bfloat16 or not hidden.is_cuda or hidden.stride(1) != 1:
+        raise TypeError("hidden must be a 2-D bf16 GPU tensor with contiguous rows")
+    d = hidden.shape[1]
+    m = w1.shape[0]
+    if w1.shape[1] != d or w2.numel() != m or (b1 is not None and b1.numel() != m):
+        raise ValueError("w1 must be [m, d], b1 and w2 [m]")
+    n = hidden.shape[0] if row_index is None else row_index.numel()
+    dev = hidden.device
+    score = torch.empty(n, dtype=torch.float32, device=dev)
+    prob = torch.empty(n, dtype=torch.float32, device=dev)
+    row_stride = hidden.stride(0) if hidden.shape[0] > 1 else max(d, hidden.stride(0))
+    rc = lib().arrol_score_mlp(hidden.data_ptr(), row_stride, _ptr(row_index, torch.int64, "row_index"),
+                               _ptr(w1, torch.bfloat16, "w1"), _ptr(b1, torch.float32, "b1"),
+                               _ptr(w2, torch.float32, "w2"), float(b2), n, d, m, score.data_ptr(), prob.data_ptr(),
+                               _stream(stream))
+    _check("arrol_score_mlp", rc)
+    return score, prob
 
 
 def arrol_select(prob, n_groups, G, K, rho=0.5, out_keep=None, out_survivors=None, stream=None):

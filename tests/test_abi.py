@@ -29,7 +29,8 @@ def test_header_declares_the_five_stage_calls():
     for fn in ["arrol_score", "arrol_select", "arrol_compact", "arrol_logprob", "arrol_weighted_vote",
                "arrol_compact_workspace_bytes", "arrol_logprob_workspace_bytes", "arrol_version",
                "arrol_error_string", "arrol_set_tuning", "arrol_histogram", "arrol_calibrate",
-               "arrol_prune_bernoulli", "arrol_compact_inplace", "arrol_compact_inplace_workspace_bytes"]:
+               "arrol_prune_bernoulli", "arrol_compact_inplace", "arrol_compact_inplace_workspace_bytes",
+               "arrol_score_mlp"]:
         assert fn in names
 
 
@@ -96,6 +97,11 @@ def test_bad_arguments_are_rejected_on_the_host(pkg):
     assert L.arrol_compact(fake, lay, far, lay, *args, None, 0, None) == -2
     assert L.arrol_compact(fake, lay, far, lay, *args, fake, 4, None) == -2
     assert L.arrol_set_tuning(b"no_such_knob", 1) == -1
+    # MLP head: bad d, m < 1, null weights
+    assert L.arrol_score_mlp(fake, 16, None, fake, None, fake, 0.0, 4, 12, 8, None, fake, None) == -1
+    assert L.arrol_score_mlp(fake, 16, None, fake, None, fake, 0.0, 4, 16, 0, None, fake, None) == -1
+    assert L.arrol_score_mlp(fake, 16, None, fake, None, None, 0.0, 4, 16, 8, None, fake, None) == -1
+    assert L.arrol_score_mlp(None, 16, None, None, None, None, 0.0, 0, 16, 8, None, None, None) == 0
     # in-place compaction: bad geometry, missing / short workspace
     assert L.arrol_compact_inplace(fake, odd, fake, fake, 4, fake, 32, 16, fake, fake, fake, fake, None, fake, 1 << 20, None) == -1
     assert L.arrol_compact_inplace(fake, lay, fake, fake, 0, fake, 32, 16, fake, fake, fake, fake, None, fake, 1 << 20, None) == -1

@@ -311,3 +311,38 @@ def test_whole_path_is_deterministic(A, W):
     for _ in range(2):
         again = A.arrol_logprob(hidden, lm_head, targets)
         assert torch.equal(first, again)
+
+
+# ------------------------------------------------------------------------------- MLP head
+@pytest.mark.parametrize("n,d,m", [(32, 256, 64), (1, 8, 1), (130, 264, 100), (512, 2048, 512), (300, 4096, 257),
+                                   (1000, 3072, 768)])
+def test_score_mlp_matches_oracle(A, n, d, m):
+    say("score_mlp n=%d d=%d m=%d" % (n, d, m))
+    g = torch.Generator(device=DEV); g.manual_seed(n + d + m)
+    hidden = torch.randn(n, d, generator=g, device=DEV).to(torch.bfloat16)
+    w1 = (torch.randn(m, d, generator=g, device=DEV) * d ** -0.5).to(torch.bfloat16)
+    b1 = torch.randn(m, generator=g, device=DEV) * 0.1
+    w2 = torch.randn(m, generator=g, device=DEV) * m ** -0.5
+    s, q = A.arrol_score_mlp(hidden, w1, b1, w2, b2=-0.125)
+    s_nb, _ = A.arrol_score_mlp(hidden, w1, None, w2)
+    torch.cuda.synchronize()
+    so, qo = O.score_mlp(bits(hidden), bits(w1), npy(b1), npy(w2), -0.125)
+    assert np.max(np.abs(npy(s) - so)) < 1e-3 and np.max(np.abs(npy(q) - qo)) < PROB_TOL
+    so_nb, _ = O.score_mlp(bits(hidden), bits(w1), np.zeros(m, np.float32), npy(w2), 0.0)
+    assert np.max(np.abs(npy(s_nb) - so_nb)) < 1e-3
+
+
+def test_score_mlp_gathered_rows_and_dead_units(A):
+    g = torch.Generator(device=DEV); g.manual_seed(8)
+    big = torch.randn(200, 512, generator=g, device=DEV).to(torch.bfloat16)
+    w1 = (torch.randn(96, 256, generator=g, device=DEV) / 16).to(torch.bfloat16)
+    w2 = torch.randn(96, generator=g, device=DEV) / 10
+    view = big[:, 256:]
+    idx = torch.tensor([199, 0, 3, 3, 150], dtype=torch.int64, device=DEV)
+    s, q = A.arrol_score_mlp(view, w1, None, w2, row_index=idx)
+    dead = torch.full((96,), -1e6, device=DEV)
+    s0, q0 = A.arrol_score_mlp(view, w1, dead, w2, b2=0.5)
+    torch.cuda.synchronize()
+    so, _ = O.score_mlp(bits(view.contiguous())[npy(idx)], bits(w1), np.zeros(96, np.float32), npy(w2), 0.0)
+    assert np.max(np.abs(npy(s) - so)) < 1e-3
+    assert torch.all(s0 == 0.5)
