@@ -13,6 +13,18 @@ static inline int arrol_launch_status() {
     return hipGetLastError() == hipSuccess ? ARROL_OK : ARROL_EHIP;
 }
 
+// Raises a kernel's dynamic-LDS limit once per device (function attributes are per device).
+template <class K>
+static inline bool arrol_allow_lds(K kernel, int bytes, bool (&done)[64]) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false;
+    if (done[dev]) return true;
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess)
+        return false;
+    done[dev] = true;
+    return true;
+}
+
 static inline bool arrol_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // 64-bit lane exchange built from two 32-bit shuffles.

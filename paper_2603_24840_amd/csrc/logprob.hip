@@ -624,15 +624,10 @@ extern "C" int arrol_logprob(const void* hidden, const void* lm_head, const int3
     if (!workspace || !arrol_aligned16(workspace) || workspace_bytes < arrol_logprob_workspace_bytes(T, V, d))
         return ARROL_EWORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    static bool attr_done = false;
-    if (!attr_done) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&logprob_kernel<MainTile>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, MainTile::LDS_BYTES) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void*>(&logprob_ring_kernel<FastTile>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, FastTile::LDS_BYTES) != hipSuccess)
-            return ARROL_EHIP;
-        attr_done = true;
-    }
+    static bool general_ok[64] = {}, fast_ok[64] = {};
+    if (!arrol_allow_lds(&logprob_kernel<MainTile>, MainTile::LDS_BYTES, general_ok) ||
+        !arrol_allow_lds(&logprob_ring_kernel<FastTile>, FastTile::LDS_BYTES, fast_ok))
+        return ARROL_EHIP;
     LogprobArgs a;
     a.H = static_cast<const uint16_t*>(hidden);
     a.W = static_cast<const uint16_t*>(lm_head);

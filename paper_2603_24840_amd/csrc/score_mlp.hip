@@ -167,13 +167,8 @@ extern "C" int arrol_score_mlp(const void* hidden, int64_t row_stride_elems, con
     if (n_rows < 0 || d < 8 || (d & 7) || m < 1 || row_stride_elems < d || (row_stride_elems & 7)) return ARROL_EINVAL;
     if (n_rows == 0) return ARROL_OK;
     if (!hidden || !w1 || !w2 || !prob_out || !arrol_aligned16(hidden) || !arrol_aligned16(w1)) return ARROL_EINVAL;
-    static bool attr_done = false;
-    if (!attr_done) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&score_mlp_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess)
-            return ARROL_EHIP;
-        attr_done = true;
-    }
+    static bool lds_ok[64] = {};
+    if (!arrol_allow_lds(&score_mlp_kernel, kLdsBytes, lds_ok)) return ARROL_EHIP;
     MlpArgs a;
     a.hidden = static_cast<const uint16_t*>(hidden); a.row_stride = row_stride_elems; a.row_index = row_index;
     a.w1 = static_cast<const uint16_t*>(w1); a.b1 = b1; a.w2 = w2; a.b2 = b2;
