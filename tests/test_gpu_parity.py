@@ -224,7 +224,7 @@ def test_logprob_tiny_config(A, W):
 
 
 @pytest.mark.parametrize("T,V,d", [(1, 1, 8), (300, 1000, 72), (257, 4097, 128), (33, 300, 200), (700, 2049, 320),
-                                   (512, 129, 64), (65, 7000, 1024)])
+                                   (512, 129, 64), (65, 7000, 1024), (100, 3000, 64), (40, 700, 128), (1030, 520, 192)])
 def test_logprob_ragged_shapes(A, T, V, d):
     say("logprob T=%d V=%d d=%d" % (T, V, d))
     g = torch.Generator(device=DEV); g.manual_seed(T * 31 + V * 7 + d)
