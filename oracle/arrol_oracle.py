@@ -421,3 +421,66 @@ def score_mlp(hidden_bits, w1_bits, b1, w2, b2=0.0):
             e = math.exp(s[i])
             q[i] = e / (1.0 + e)
     return s, q
+
+
+# ----------------------------------------------------------------------------
+# quality-head training: cross-entropy loss, its gradient, optimizer step
+# ----------------------------------------------------------------------------
+def _log_sigmoid(s):
+    """log(sigmoid(s)) without overflow."""
+    return -math.log1p(math.exp(-s)) if s >= 0.0 else s - math.log1p(math.exp(s))
+
+
+def score_ce(hidden_bits, w, bias, labels):
+    """Cross-entropy loss of the linear quality head against the final rewards (Sec. 4.2 and Sec. 4.3 (iii):
+    the head is trained on the fly with a cross-entropy loss on the rollouts' rewards, the backbone's
+    hidden state being a constant).  With q_i = sigmoid(<w, h_i> + bias) and label y_i in [0, 1]:
+        L = -(1/N) sum_i [ y_i log q_i + (1 - y_i) log(1 - q_i) ]
+    Returns L as a float (float64 arithmetic on the exact input values)."""
+    h = bf16_bits_to_f64(hidden_bits)
+    w = np.asarray(w, dtype=np.float32).astype(np.float64)
+    y = np.asarray(labels, dtype=np.float32).astype(np.float64)
+    n = h.shape[0]
+    terms = []
+    for i in range(n):
+        s = math.fsum(h[i] * w) + float(bias)
+        terms.append(-(y[i] * _log_sigmoid(s) + (1.0 - y[i]) * _log_sigmoid(-s)))
+    return math.fsum(terms) / n
+
+
+def score_ce_grad(hidden_bits, w, bias, labels):
+    """Gradient of score_ce with respect to the head's parameters (the hidden states carry no gradient:
+    Sec. 4.3 (iii) stops it at the backbone).  dL/ds_i = (q_i - y_i)/N, hence
+        dL/dw = (1/N) sum_i (q_i - y_i) h_i,   dL/dbias = (1/N) sum_i (q_i - y_i).
+    Returns (loss, grad_w float64 [d], grad_bias float)."""
+    h = bf16_bits_to_f64(hidden_bits)
+    wv = np.asarray(w, dtype=np.float32).astype(np.float64)
+    y = np.asarray(labels, dtype=np.float32).astype(np.float64)
+    n, d = h.shape
+    r = np.empty(n, dtype=np.float64)
+    for i in range(n):
+        s = math.fsum(h[i] * wv) + float(bias)
+        q = 1.0 / (1.0 + math.exp(-s)) if s >= 0.0 else math.exp(s) / (1.0 + math.exp(s))
+        r[i] = q - y[i]
+    grad_w = np.array([math.fsum(r * h[:, c]) for c in range(d)], dtype=np.float64) / n
+    return score_ce(hidden_bits, w, bias, labels), grad_w, math.fsum(r) / n
+
+
+def adamw_step(param, grad, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0):
+    """One AdamW update (Alg. 1 asks for an "optimizer step" on the quality head and names no optimizer;
+    AdamW with decoupled weight decay, Loshchilov & Hutter 2019, is this build's reading):
+        m <- b1 m + (1-b1) g;  v <- b2 v + (1-b2) g^2
+        p <- p - lr * ( (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps) + wd * p )
+    `step` is t >= 1.  Inputs are taken at the precision they come in (fp32 from the library's buffers,
+    float64 when a test carries the state over several steps); arithmetic in float64.
+    Returns (param, m, v) float64."""
+    p = np.asarray(param, dtype=np.float64)
+    g = np.asarray(grad, dtype=np.float64)
+    m = np.asarray(m, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    m = beta1 * m + (1.0 - beta1) * g
+    v = beta2 * v + (1.0 - beta2) * g * g
+    m_hat = m / (1.0 - beta1 ** step)
+    v_hat = v / (1.0 - beta2 ** step)
+    p = p - lr * (m_hat / (np.sqrt(v_hat) + eps) + weight_decay * p)
+    return p, m, v

@@ -645,3 +645,96 @@ def test_score_mlp_exact_rational():
             if pre > 0:
                 tot += pre * Fraction(float(w2[u]))
         assert abs(s[i] - float(tot)) < 1e-13
+
+
+# ----------------------------------------------------------------------------- head training
+def _head_case(seed, n=24, d=16, scale=0.5):
+    rng = np.random.default_rng(seed)
+    hb = f32_to_bf16_bits(rng.normal(size=(n, d)).astype(np.float32))
+    w = (rng.normal(size=d) * scale).astype(np.float32)
+    y = (rng.random(n) < 0.4).astype(np.float32)
+    return hb, w, np.float32(rng.normal() * 0.3), y
+
+
+def test_score_ce_at_zero_weights_is_ln2_and_gradient_is_the_label_offset():
+    hb, w, _, y = _head_case(11)
+    loss, gw, gb = O.score_ce_grad(hb, np.zeros_like(w), 0.0, y)
+    assert abs(loss - math.log(2.0)) < 1e-15
+    h = O.bf16_bits_to_f64(hb)
+    assert np.allclose(gw, ((0.5 - y.astype(np.float64))[:, None] * h).mean(axis=0), rtol=0, atol=1e-15)
+    assert abs(gb - float(np.mean(0.5 - y.astype(np.float64)))) < 1e-15
+
+
+def test_score_ce_matches_the_definition_through_the_probabilities():
+    # L = -mean(y log q + (1-y) log(1-q)) with q taken from the scoring oracle
+    hb, w, b, y = _head_case(12)
+    _, q = O.score(hb, w, b)
+    y64 = y.astype(np.float64)
+    direct = -np.mean(y64 * np.log(q) + (1.0 - y64) * np.log(1.0 - q))
+    assert abs(O.score_ce(hb, w, b, y) - direct) < 1e-12
+
+
+def test_score_ce_gradient_against_central_differences():
+    hb, w, b, y = _head_case(13, n=20, d=8)
+    loss, gw, gb = O.score_ce_grad(hb, w, b, y)
+    assert abs(loss - O.score_ce(hb, w, b, y)) == 0.0
+    # float32 parameters: step by whole fp32 increments so that w +- e is representable
+    for c in range(8):
+        e = np.float32(2.0 ** -7)
+        wp, wm = w.copy(), w.copy()
+        wp[c] = w[c] + e
+        wm[c] = w[c] - e
+        step = float(wp[c]) - float(wm[c])
+        fd = (O.score_ce(hb, wp, b, y) - O.score_ce(hb, wm, b, y)) / step
+        assert abs(fd - gw[c]) < 5e-5, (c, fd, gw[c])
+    e = 2.0 ** -7
+    fd = (O.score_ce(hb, w, float(b) + e, y) - O.score_ce(hb, w, float(b) - e, y)) / (2 * e)
+    assert abs(fd - gb) < 5e-5
+
+
+def test_score_ce_soft_labels_equal_to_the_prediction_have_zero_gradient():
+    hb, w, b, _ = _head_case(14)
+    _, q = O.score(hb, w, b)
+    # labels are read as fp32, so the match is to fp32 rounding of q
+    loss, gw, gb = O.score_ce_grad(hb, w, b, q.astype(np.float32))
+    assert np.max(np.abs(gw)) < 1e-6 and abs(gb) < 1e-7
+    # and the loss is then the mean binary entropy of q
+    ent = -np.mean(q * np.log(q) + (1 - q) * np.log(1 - q))
+    assert abs(loss - ent) < 1e-6
+
+
+def test_score_ce_saturated_logits_stay_finite():
+    hb = f32_to_bf16_bits(np.full((2, 8), 16.0, dtype=np.float32))
+    w = np.full(8, 8.0, dtype=np.float32)                     # s = 1024
+    loss, gw, gb = O.score_ce_grad(hb, w, 0.0, np.array([1.0, 0.0], dtype=np.float32))
+    assert math.isfinite(loss) and abs(loss - 512.0) < 1e-9   # (0 + 1024)/2
+    assert np.allclose(gw, 0.5 * 16.0) and abs(gb - 0.5) < 1e-12
+
+
+def test_adamw_first_step_closed_form():
+    # with zero state, m_hat = g and v_hat = g^2, so the step is lr*(g/(|g|+eps) + wd*p)
+    p = np.array([1.0, -2.0, 0.5, 3.0], dtype=np.float32)
+    g = np.array([0.25, -4.0, 0.0, 1e-3], dtype=np.float32)
+    z = np.zeros(4, dtype=np.float32)
+    p1, m1, v1 = O.adamw_step(p, g, z, z, 1, lr=0.1, beta1=0.9, beta2=0.99, eps=1e-8, weight_decay=0.01)
+    g64, p64 = g.astype(np.float64), p.astype(np.float64)
+    want = p64 - 0.1 * (g64 / (np.abs(g64) + 1e-8) + 0.01 * p64)
+    assert np.allclose(p1, want, rtol=0, atol=1e-12)
+    assert np.allclose(m1, 0.1 * g64, atol=1e-15) and np.allclose(v1, 0.01 * g64 * g64, atol=1e-15)
+
+
+def test_adamw_matches_the_library_optimizer_over_several_steps():
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(5)
+    p0 = rng.normal(size=33).astype(np.float32)
+    grads = [rng.normal(size=33).astype(np.float32) * (10.0 ** rng.integers(-3, 2)) for _ in range(6)]
+    tp = torch.nn.Parameter(torch.tensor(p0, dtype=torch.float64))
+    opt = torch.optim.AdamW([tp], lr=3e-2, betas=(0.8, 0.95), eps=1e-6, weight_decay=0.1)
+    p = p0.astype(np.float64)
+    m = np.zeros(33)
+    v = np.zeros(33)
+    for t, g in enumerate(grads, start=1):
+        tp.grad = torch.tensor(g, dtype=torch.float64)
+        opt.step()
+        p, m, v = O.adamw_step(p, g, m, v, t, 3e-2, 0.8, 0.95, 1e-6, 0.1)
+        assert np.allclose(p, tp.detach().numpy(), rtol=1e-12, atol=1e-12), t
