@@ -234,6 +234,38 @@ int arrol_prune_bernoulli(const float* s_norm, const float* uniforms, int32_t N,
                           int32_t* n_survivors, void* stream);
 
 /*
+ * ---- Training the quality head (Sec. 4.2; Sec. 4.3 (iii); Alg. 1 "optimizer step on policy and quality head") ----
+ * The head is fitted on the fly to the rollouts' final rewards with a cross-entropy loss; the hidden states
+ * are constants (no gradient reaches the backbone).  For the linear head, with q_i = sigmoid(<w,h_i> + bias):
+ *   L = -(1/N) sum_i [ y_i log q_i + (1-y_i) log(1-q_i) ]
+ *   dL/dw = (1/N) sum_i (q_i - y_i) h_i,   dL/dbias = (1/N) sum_i (q_i - y_i)
+ * hidden, row_stride_elems, row_index, w, bias as in arrol_score; labels fp32 [n_rows] in [0,1] (the reward
+ * of output row i).  8 <= d <= 8192, d a multiple of 8.
+ * loss_out NULL or fp32 [1]; grad_w fp32 [d]; grad_bias NULL or fp32 [1].  fp32 arithmetic, sums in a fixed
+ * order (bit-reproducible run to run).  n_rows == 0 writes zeros.
+ * workspace: device memory of at least arrol_score_grad_workspace_bytes(n_rows, d), caller-owned, contents
+ * undefined afterwards; too small or NULL -> ARROL_EWORKSPACE.
+ */
+size_t arrol_score_grad_workspace_bytes(int32_t n_rows, int32_t d);
+int arrol_score_grad(const void* hidden, int64_t row_stride_elems, const int64_t* row_index,
+                     const float* w, float bias, const float* labels, int32_t n_rows, int32_t d,
+                     float* loss_out, float* grad_w, float* grad_bias, void* workspace,
+                     size_t workspace_bytes, void* stream);
+
+/*
+ * One AdamW update in place (the paper names no optimizer; AdamW with decoupled weight decay is this
+ * build's reading).  With t = step >= 1:
+ *   m <- beta1 m + (1-beta1) g;  v <- beta2 v + (1-beta2) g^2
+ *   p <- p - lr * ( (m/(1-beta1^t)) / (sqrt(v/(1-beta2^t)) + eps) + weight_decay * p )
+ * param, m, v fp32 [n] updated in place; grad fp32 [n]; all device pointers.  param_bf16: NULL, or bf16 [n]
+ * that receives the updated parameters rounded to nearest even (the copy arrol_score_mlp reads).
+ * 0 <= beta1, beta2 < 1, eps >= 0, else ARROL_EINVAL.  n == 0 is a no-op.
+ */
+int arrol_adamw_step(float* param, const float* grad, float* m, float* v, int64_t n, int32_t step,
+                     float lr, float beta1, float beta2, float eps, float weight_decay,
+                     void* param_bf16, void* stream);
+
+/*
  * Benchmarking knob, not a stage of the method.  key "logprob_splits": number of vocabulary
  * splits arrol_logprob uses (0 = built-in heuristic).  Process-wide, not thread-safe; the
  * workspace size must be queried again after changing it.  Unknown key: ARROL_EINVAL.

@@ -45,6 +45,9 @@ _SIGNATURES = {
     "arrol_set_tuning": (ctypes.c_int, [ctypes.c_char_p, ctypes.c_int]),
     "arrol_score": (ctypes.c_int, [_vp, _i64, _vp, _vp, _f32, _i32, _i32, _vp, _vp, _vp]),
     "arrol_score_mlp": (ctypes.c_int, [_vp, _i64, _vp, _vp, _vp, _vp, _f32, _i32, _i32, _i32, _vp, _vp, _vp]),
+    "arrol_score_grad_workspace_bytes": (_sz, [_i32, _i32]),
+    "arrol_score_grad": (ctypes.c_int, [_vp, _i64, _vp, _vp, _f32, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "arrol_adamw_step": (ctypes.c_int, [_vp, _vp, _vp, _vp, _i64, _i32, _f32, _f32, _f32, _f32, _f32, _vp, _vp]),
     "arrol_select": (ctypes.c_int, [_vp, _i32, _i32, _i32, _f32, _vp, _vp, _vp]),
     "arrol_compact_workspace_bytes": (_sz, [_i32]),
     "arrol_compact": (ctypes.c_int, [_vp, KVLayout, _vp, KVLayout, _vp, _vp, _i32, _vp, _i32, _vp, _i32, _i32,
@@ -154,6 +157,45 @@ def arrol_score_mlp(hidden, w1, b1, w2, b2=0.0, row_index=None, stream=None):
                                _stream(stream))
     _check("arrol_score_mlp", rc)
     return score, prob
+
+
+def arrol_score_grad(hidden, w, bias, labels, row_index=None, workspace=None, stream=None):
+    """Cross-entropy loss of the linear head and its gradient: hidden bf16 [R, d], w fp32 [d], labels fp32 [n]
+    -> (loss fp32 [1], grad_w fp32 [d], grad_bias fp32 [1])."""
+    if hidden.dim() != 2 or hidden.dtype != torch.bfloat16 or not hidden.is_cuda or hidden.stride(1) != 1:
+        raise TypeError("hidden must be a 2-D bf16 GPU tensor with contiguous rows")
+    d = hidden.shape[1]
+    n = hidden.shape[0] if row_index is None else row_index.numel()
+    if labels.numel() != n or w.numel() != d:
+        raise ValueError("labels must be [n] and w [d]")
+    dev = hidden.device
+    need = lib().arrol_score_grad_workspace_bytes(n, d)
+    if workspace is None:
+        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=dev)
+    loss = torch.empty(1, dtype=torch.float32, device=dev)
+    grad_w = torch.empty(d, dtype=torch.float32, device=dev)
+    grad_b = torch.empty(1, dtype=torch.float32, device=dev)
+    row_stride = hidden.stride(0) if hidden.shape[0] > 1 else max(d, hidden.stride(0))
+    rc = lib().arrol_score_grad(hidden.data_ptr(), row_stride, _ptr(row_index, torch.int64, "row_index"),
+                                _ptr(w, torch.float32, "w"), float(bias), _ptr(labels, torch.float32, "labels"), n, d,
+                                loss.data_ptr(), grad_w.data_ptr(), grad_b.data_ptr(),
+                                _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
+    _check("arrol_score_grad", rc)
+    return loss, grad_w, grad_b
+
+
+def arrol_adamw_step(param, grad, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0,
+                     param_bf16=None, stream=None):
+    """In-place AdamW update of fp32 param / m / v (all [n]); param_bf16 (optional, bf16 [n]) gets a rounded copy."""
+    n = param.numel()
+    if grad.numel() != n or m.numel() != n or v.numel() != n or (param_bf16 is not None and param_bf16.numel() != n):
+        raise ValueError("param, grad, m, v (and param_bf16) must have the same number of elements")
+    rc = lib().arrol_adamw_step(_ptr(param, torch.float32, "param"), _ptr(grad, torch.float32, "grad"),
+                                _ptr(m, torch.float32, "m"), _ptr(v, torch.float32, "v"), n, int(step), float(lr),
+                                float(beta1), float(beta2), float(eps), float(weight_decay),
+                                _ptr(param_bf16, torch.bfloat16, "param_bf16"), _stream(stream))
+    _check("arrol_adamw_step", rc)
+    return param
 
 
 def arrol_select(prob, n_groups, G, K, rho=0.5, out_keep=None, out_survivors=None, stream=None):

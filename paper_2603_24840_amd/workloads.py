@@ -92,6 +92,18 @@ def score_inputs(cfg, device, n_rows=None):
     return hidden, w, 0.0
 
 
+def head_training_inputs(cfg, device, n_rows=None):
+    """Labelled hidden states for one update of the quality head: hidden / head weights as in score_inputs;
+    the reward label of a row is 1 with probability sigmoid(2 <w*, h>) for a hidden "true" direction w*,
+    so labels correlate with the hidden state but the current head (w) does not yet predict them."""
+    hidden, w, bias = score_inputs(cfg, device, n_rows)
+    g = _gen(cfg, 9, device)
+    w_true = torch.randn(cfg.d, generator=g, device=device, dtype=torch.float32) * (cfg.d ** -0.5)
+    p_true = torch.sigmoid(2.0 * (hidden.float() @ w_true))
+    labels = (torch.rand(hidden.shape[0], generator=g, device=device) < p_true).to(torch.float32)
+    return hidden, w, bias, labels
+
+
 def select_inputs(cfg, device):
     """Probabilities as the sigmoid of N(0,1) scores (what stage 1 yields at these shapes)."""
     g = _gen(cfg, 2, device)

@@ -30,7 +30,7 @@ def test_header_declares_the_five_stage_calls():
                "arrol_compact_workspace_bytes", "arrol_logprob_workspace_bytes", "arrol_version",
                "arrol_error_string", "arrol_set_tuning", "arrol_histogram", "arrol_calibrate",
                "arrol_prune_bernoulli", "arrol_compact_inplace", "arrol_compact_inplace_workspace_bytes",
-               "arrol_score_mlp"]:
+               "arrol_score_mlp", "arrol_score_grad", "arrol_score_grad_workspace_bytes", "arrol_adamw_step"]:
         assert fn in names
 
 
@@ -102,6 +102,18 @@ def test_bad_arguments_are_rejected_on_the_host(pkg):
     assert L.arrol_score_mlp(fake, 16, None, fake, None, fake, 0.0, 4, 16, 0, None, fake, None) == -1
     assert L.arrol_score_mlp(fake, 16, None, fake, None, None, 0.0, 4, 16, 8, None, fake, None) == -1
     assert L.arrol_score_mlp(None, 16, None, None, None, None, 0.0, 0, 16, 8, None, None, None) == 0
+    # head training: bad d, missing gradient output, workspace; optimizer: bad step / betas
+    assert L.arrol_score_grad(fake, 16, None, fake, 0.0, fake, 4, 12, None, fake, None, fake, 1 << 20, None) == -1
+    assert L.arrol_score_grad(fake, 16384, None, fake, 0.0, fake, 4, 16384, None, fake, None, fake, 1 << 20, None) == -1
+    assert L.arrol_score_grad(fake, 16, None, fake, 0.0, fake, 4, 16, None, None, None, fake, 1 << 20, None) == -1
+    assert L.arrol_score_grad(fake, 16, None, fake, 0.0, None, 4, 16, None, fake, None, fake, 1 << 20, None) == -1
+    assert L.arrol_score_grad(fake, 16, None, fake, 0.0, fake, 4, 16, None, fake, None, None, 0, None) == -2
+    assert L.arrol_score_grad(fake, 16, None, fake, 0.0, fake, 4, 16, None, fake, None, fake, 8, None) == -2
+    assert L.arrol_score_grad_workspace_bytes(4, 16) >= (16 + 2) * 4
+    assert L.arrol_adamw_step(fake, fake, fake, fake, 8, 0, 1e-3, 0.9, 0.999, 1e-8, 0.0, None, None) == -1
+    assert L.arrol_adamw_step(fake, fake, fake, fake, 8, 1, 1e-3, 1.0, 0.999, 1e-8, 0.0, None, None) == -1
+    assert L.arrol_adamw_step(fake, None, fake, fake, 8, 1, 1e-3, 0.9, 0.999, 1e-8, 0.0, None, None) == -1
+    assert L.arrol_adamw_step(None, None, None, None, 0, 1, 1e-3, 0.9, 0.999, 1e-8, 0.0, None, None) == 0
     # in-place compaction: bad geometry, missing / short workspace
     assert L.arrol_compact_inplace(fake, odd, fake, fake, 4, fake, 32, 16, fake, fake, fake, fake, None, fake, 1 << 20, None) == -1
     assert L.arrol_compact_inplace(fake, lay, fake, fake, 0, fake, 32, 16, fake, fake, fake, fake, None, fake, 1 << 20, None) == -1

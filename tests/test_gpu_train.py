@@ -1,0 +1,142 @@
+"""Parity of the quality-head training calls (cross-entropy loss + gradient, AdamW) with the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from helpers import bits, npy
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+# fp32 sums of N terms (|r_i h_ic| <= ~5) in a tree of depth N/grid + log: error ~ 1e-7 * sqrt(N) * 5 / N
+# relative to a mean of magnitude <= 1; the bound below leaves two orders of margin at every size tested.
+GRAD_ATOL, GRAD_RTOL = 2e-6, 2e-5
+LOSS_RTOL = 2e-6
+
+
+@pytest.fixture(scope="module")
+def A():
+    import paper_2603_24840_amd as pkg
+    pkg.lib()
+    return pkg
+
+
+@pytest.fixture(scope="module")
+def W():
+    from paper_2603_24840_amd import workloads
+    return workloads
+
+
+def check_grad(A, hidden, w, bias, labels, row_index=None):
+    loss, gw, gb = A.arrol_score_grad(hidden, w, bias, labels, row_index=row_index)
+    torch.cuda.synchronize()
+    hb = bits(hidden)
+    if row_index is not None:
+        hb = hb[npy(row_index)]
+    loss_o, gw_o, gb_o = O.score_ce_grad(hb, npy(w), np.float32(bias), npy(labels))
+    assert abs(float(loss) - loss_o) <= LOSS_RTOL * max(1.0, abs(loss_o)), (float(loss), loss_o)
+    err = np.abs(npy(gw).astype(np.float64) - gw_o)
+    assert np.all(err <= GRAD_ATOL + GRAD_RTOL * np.abs(gw_o)), float(err.max())
+    assert abs(float(gb) - gb_o) <= GRAD_ATOL + GRAD_RTOL * abs(gb_o)
+    return loss, gw, gb
+
+
+@pytest.mark.parametrize("n,d", [(1, 8), (7, 24), (64, 512), (65, 520), (300, 1024), (513, 2048), (200, 3072),
+                                 (130, 4096), (70, 8192), (90, 5000 // 8 * 8)])
+def test_score_grad_matches_oracle(A, W, n, d):
+    print("[case] score_grad n=%d d=%d" % (n, d), flush=True)
+    cfg = W.shrink(W.CONFIGS["tiny"], d=d)
+    hidden, w, _, labels = W.head_training_inputs(cfg, DEV, n_rows=n)
+    check_grad(A, hidden, w * 3.0, 0.25, labels)
+
+
+def test_score_grad_row_index_strided_rows_and_soft_labels(A, W):
+    print("[case] score_grad row_index/strided/soft", flush=True)
+    cfg = W.shrink(W.CONFIGS["tiny"], d=256)
+    big, w, _, _ = W.head_training_inputs(cfg, DEV, n_rows=400)
+    wide = torch.zeros(400, 320, dtype=torch.bfloat16, device=DEV)
+    wide[:, :256] = big
+    view = wide[:, :256]                                   # row stride 320 elements
+    g = torch.Generator(device=DEV); g.manual_seed(3)
+    idx = torch.randint(0, 400, (150,), generator=g, device=DEV, dtype=torch.int64)
+    soft = torch.rand(150, generator=g, device=DEV)
+    check_grad(A, view, w, -0.5, soft, row_index=idx)
+
+
+def test_score_grad_many_rows_uses_every_workgroup_and_is_reproducible(A, W):
+    print("[case] score_grad n=70000 d=128", flush=True)
+    cfg = W.shrink(W.CONFIGS["tiny"], d=128)
+    hidden, w, _, labels = W.head_training_inputs(cfg, DEV, n_rows=70_000)   # > 1024 workgroups * 64 rows
+    l1, g1, b1 = check_grad(A, hidden, w * 2.0, 0.0, labels)
+    l2, g2, b2 = A.arrol_score_grad(hidden, w * 2.0, 0.0, labels)
+    torch.cuda.synchronize()
+    assert torch.equal(g1, g2) and torch.equal(l1, l2) and torch.equal(b1, b2)
+
+
+def test_score_grad_saturated_logits_and_empty_batch(A):
+    print("[case] score_grad saturated / empty", flush=True)
+    hidden = torch.full((2, 8), 16.0, dtype=torch.bfloat16, device=DEV)
+    w = torch.full((8,), 8.0, device=DEV)
+    labels = torch.tensor([1.0, 0.0], device=DEV)
+    loss, gw, gb = A.arrol_score_grad(hidden, w, 0.0, labels)
+    torch.cuda.synchronize()
+    assert float(loss) == 512.0 and torch.all(gw == 8.0) and float(gb) == 0.5
+    loss, gw, gb = A.arrol_score_grad(hidden[:0], w, 0.0, labels[:0])
+    torch.cuda.synchronize()
+    assert float(loss) == 0.0 and torch.all(gw == 0.0) and float(gb) == 0.0
+
+
+def test_score_grad_full_training_shape(A, W):
+    """The head's update at the benchmark configuration: every rollout of a step, d = 2048."""
+    cfg = W.CONFIGS["llama1b"]
+    print("[case] score_grad full n=%d d=%d" % (cfg.n_rollouts, cfg.d), flush=True)
+    hidden, w, _, labels = W.head_training_inputs(cfg, DEV)
+    check_grad(A, hidden, w, 0.0, labels)
+
+
+@pytest.mark.parametrize("n", [1, 255, 4096, 1_000_003])
+def test_adamw_matches_oracle_over_three_steps(A, n):
+    print("[case] adamw n=%d" % n, flush=True)
+    g = torch.Generator(device=DEV); g.manual_seed(n)
+    p = torch.randn(n, generator=g, device=DEV)
+    m = torch.zeros(n, device=DEV)
+    v = torch.zeros(n, device=DEV)
+    pb = torch.empty(n, dtype=torch.bfloat16, device=DEV)
+    hp = dict(lr=1e-2, beta1=0.9, beta2=0.99, eps=1e-8, weight_decay=0.05)
+    for t in (1, 2, 3):
+        grad = torch.randn(n, generator=g, device=DEV) * (10.0 ** (t - 2))
+        p0, m0, v0 = npy(p), npy(m), npy(v)
+        A.arrol_adamw_step(p, grad, m, v, t, param_bf16=pb, **hp)
+        torch.cuda.synchronize()
+        f = lambda x: float(np.float32(x))
+        p_o, m_o, v_o = O.adamw_step(p0, npy(grad), m0, v0, t, f(1e-2), f(0.9), f(0.99), f(1e-8), f(0.05))
+        g64 = np.abs(npy(grad).astype(np.float64))
+        # m adds two rounded products that may cancel: the error scales with the operands, not the result
+        assert np.all(np.abs(npy(m) - m_o) <= 4e-7 * (np.abs(m0) + g64)), "m"
+        assert np.all(np.abs(npy(v) - v_o) <= 1e-6 * v_o), "v"
+        assert np.all(np.abs(npy(p) - p_o) <= 1e-7 + 2e-6 * np.abs(p_o)), "p"
+        # the bf16 copy is the round-to-nearest-even image of the fp32 parameters the call stored
+        from helpers import f32_to_bf16_bits
+        assert np.array_equal(bits(pb), f32_to_bf16_bits(npy(p)))
+
+
+def test_head_training_loop_reduces_the_loss(A, W):
+    """End to end: gradient + AdamW for a few steps lowers the cross-entropy on the same batch, and the
+    trajectory stays on the oracle's (loss after five steps within 1e-4 relative)."""
+    print("[case] training loop", flush=True)
+    cfg = W.shrink(W.CONFIGS["tiny"], d=64)
+    hidden, w, _, labels = W.head_training_inputs(cfg, DEV, n_rows=512)
+    w = w.clone()
+    b = torch.zeros(1, device=DEV)
+    m, v = torch.zeros_like(w), torch.zeros_like(w)
+    w_o, m_o, v_o = npy(w).astype(np.float64), np.zeros(64), np.zeros(64)
+    hb, y = bits(hidden), npy(labels)
+    losses = []
+    for t in range(1, 6):
+        loss, gw, _ = A.arrol_score_grad(hidden, w, 0.0, labels)
+        A.arrol_adamw_step(w, gw, m, v, t, lr=5e-2)
+        losses.append(float(loss))
+        lo, gwo, _ = O.score_ce_grad(hb, w_o.astype(np.float32), 0.0, y)
+        w_o, m_o, v_o = O.adamw_step(w_o.astype(np.float32), gwo.astype(np.float32), m_o, v_o, t, float(np.float32(5e-2)))
+        assert abs(losses[-1] - lo) <= 1e-4 * lo
+    assert losses[-1] < losses[0]
