@@ -3,4 +3,5 @@ from .arrol_oracle import (bf16_bits_to_f64, score, quantise, select_group, sele
                            compact, log_softmax_rows, logprob, weighted_vote,
                            FIXED_POINT_BITS, bin_index, histogram, posterior_lut, bin_weights,
                            survival_lut, calibrate, prune_bernoulli, compact_inplace, score_mlp,
-                           score_ce, score_ce_grad, adamw_step)
+                           score_ce, score_ce_grad, adamw_step,
+                           token_confidence, trace_confidence)

@@ -19,6 +19,8 @@ Stages (paper passages in each docstring):
   logprob        log pi(o_t | o_<t)                Sec. 3 (GRPO ratio); Alg. 1
   weighted_vote  rank-weighted answer vote         Sec. 4.4
   histogram / calibrate / prune_bernoulli   the practical policy   App. A.4 Eq. 1-2; Alg. 1
+  score_mlp, score_ce(_grad), adamw_step    quality head variants and training   Sec. 4.2, 4.3 (iii)
+  token_confidence / trace_confidence       trace confidence   Sec. 3
 """
 import math
 
@@ -484,3 +486,51 @@ def adamw_step(param, grad, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e-8, we
     v_hat = v / (1.0 - beta2 ** step)
     p = p - lr * (m_hat / (np.sqrt(v_hat) + eps) + weight_decay * p)
     return p, m, v
+
+
+# ----------------------------------------------------------------------------
+# trace confidence (Sec. 3, "Trace Confidence")
+# ----------------------------------------------------------------------------
+def token_confidence(hidden_bits, lm_head_bits):
+    """Token confidence of Sec. 3: H_t = - sum_{j=1..V} log P_t(j), with P_t the softmax of the logits
+    z_t = W h_t (temperature 1).  Written as the definition: every log-probability is formed, then summed.
+    hidden_bits [T, d] uint16, lm_head_bits [V, d] uint16.  Returns float64 [T]."""
+    T = hidden_bits.shape[0]
+    W = bf16_bits_to_f64(lm_head_bits)
+    out = np.empty(T, dtype=np.float64)
+    for t in range(T):
+        z = W @ bf16_bits_to_f64(hidden_bits[t])
+        m = float(z.max())
+        lse = m + math.log(math.fsum(np.exp(z - m)))
+        out[t] = -math.fsum(z - lse)
+    return out
+
+
+def trace_confidence(conf, cu_seqlens, window, bottom_percent=10):
+    """Trace-level aggregates of the token confidences (Sec. 3): for each trace i = tokens
+    [cu[i], cu[i+1]):
+      mean_i    the average token confidence over the trace (the self-uncertainty score),
+      windows   H_w = mean of H_t over each run of `window` consecutive tokens (sliding by one token);
+                a trace shorter than the window has the single window "the whole trace",
+      min_i     the smallest window value,
+      bottom_i  the average of the lowest ceil(bottom_percent/100 * n_windows) window values (at least
+                one; integer arithmetic).
+    An empty trace yields NaN.  conf float [T]; cu_seqlens int [n+1].  Returns three float64 [n] arrays."""
+    conf = np.asarray(conf, dtype=np.float64)
+    cu = np.asarray(cu_seqlens, dtype=np.int64)
+    n = cu.shape[0] - 1
+    mean = np.full(n, np.nan)
+    wmin = np.full(n, np.nan)
+    bottom = np.full(n, np.nan)
+    for i in range(n):
+        x = conf[cu[i]:cu[i + 1]]
+        L = x.shape[0]
+        if L == 0:
+            continue
+        mean[i] = math.fsum(x) / L
+        w = min(int(window), L)
+        vals = sorted(math.fsum(x[k:k + w]) / w for k in range(L - w + 1))
+        wmin[i] = vals[0]
+        m = max(1, (len(vals) * int(bottom_percent) + 99) // 100)
+        bottom[i] = math.fsum(vals[:m]) / m
+    return mean, wmin, bottom

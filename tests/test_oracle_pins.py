@@ -738,3 +738,93 @@ def test_adamw_matches_the_library_optimizer_over_several_steps():
         opt.step()
         p, m, v = O.adamw_step(p, g, m, v, t, 3e-2, 0.8, 0.95, 1e-6, 0.1)
         assert np.allclose(p, tp.detach().numpy(), rtol=1e-12, atol=1e-12), t
+
+
+# ----------------------------------------------------------------------------- trace confidence
+def test_token_confidence_uniform_distribution_is_V_ln_V_and_is_the_minimum():
+    rng = np.random.default_rng(21)
+    V, d = 37, 8
+    Wb = f32_to_bf16_bits(rng.normal(size=(V, d)).astype(np.float32))
+    zero_h = np.zeros((1, d), dtype=np.uint16)
+    assert abs(O.token_confidence(zero_h, Wb)[0] - V * math.log(V)) < 1e-10
+    # H_t / V - ln V is KL(uniform || P_t) >= 0
+    hb = f32_to_bf16_bits(rng.normal(size=(6, d)).astype(np.float32))
+    assert np.all(O.token_confidence(hb, Wb) > V * math.log(V))
+
+
+def test_token_confidence_two_token_vocabulary_closed_form():
+    # V = 2 with logits (a, b): H = log(1+e^{b-a}) + log(1+e^{a-b})
+    Wb = f32_to_bf16_bits(np.array([[1.5, 0.0], [0.0, -0.75]], dtype=np.float32))
+    hb = f32_to_bf16_bits(np.array([[2.0, 4.0], [-1.0, 0.5]], dtype=np.float32))
+    got = O.token_confidence(hb, Wb)
+    for t, (a, b) in enumerate([(3.0, -3.0), (-1.5, -0.375)]):
+        want = math.log1p(math.exp(b - a)) + math.log1p(math.exp(a - b))
+        assert abs(got[t] - want) < 1e-12
+
+
+def test_token_confidence_equals_V_lse_minus_the_logit_sum_and_matches_logprob():
+    rng = np.random.default_rng(22)
+    V, d, T = 50, 16, 5
+    Wb = f32_to_bf16_bits(rng.normal(size=(V, d)).astype(np.float32))
+    hb = f32_to_bf16_bits(rng.normal(size=(T, d)).astype(np.float32))
+    got = O.token_confidence(hb, Wb)
+    z = O.bf16_bits_to_f64(hb) @ O.bf16_bits_to_f64(Wb).T
+    _, lse = O.logprob(hb, Wb, np.zeros(T, dtype=np.int64))
+    assert np.allclose(got, V * lse - z.sum(axis=1), rtol=1e-13)
+    # summing the per-target log-probabilities over every target gives the same number
+    total = np.zeros(T)
+    for j in range(V):
+        lp, _ = O.logprob(hb, Wb, np.full(T, j))
+        total -= lp
+    assert np.allclose(got, total, rtol=1e-13)
+
+
+def test_trace_confidence_ramp_closed_forms():
+    # conf_t = t on one trace of length 100, window 10: window k has mean k + 4.5, 91 windows,
+    # bottom 10 % = ceil(9.1) = 10 lowest windows -> mean of 4.5 .. 13.5 = 9.0
+    conf = np.arange(100, dtype=np.float64)
+    mean, wmin, bottom = O.trace_confidence(conf, [0, 100], 10)
+    assert mean[0] == 49.5 and wmin[0] == 4.5 and bottom[0] == 9.0
+    # decreasing ramp: the lowest windows are the last ones
+    mean, wmin, bottom = O.trace_confidence(conf[::-1].copy(), [0, 100], 10)
+    assert mean[0] == 49.5 and wmin[0] == 4.5 and bottom[0] == 9.0
+
+
+def test_trace_confidence_window_one_and_whole_trace_windows():
+    rng = np.random.default_rng(23)
+    conf = rng.normal(size=57) * 3 + 10
+    mean, wmin, bottom = O.trace_confidence(conf, [0, 57], 1)
+    srt = np.sort(conf)
+    assert wmin[0] == srt[0] and abs(bottom[0] - srt[:6].mean()) < 1e-13     # ceil(5.7) = 6
+    for w in (57, 58, 4096):
+        mean, wmin, bottom = O.trace_confidence(conf, [0, 57], w)
+        assert abs(mean[0] - conf.mean()) < 1e-13 and wmin[0] == mean[0] == bottom[0]
+
+
+def test_trace_confidence_ragged_batch_empty_trace_and_exact_rational_brute_force():
+    rng = np.random.default_rng(24)
+    lens = [0, 1, 5, 12, 30, 3]
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    conf = rng.integers(-50, 50, size=cu[-1]).astype(np.float64) / 4      # exact quarters
+    w = 4
+    mean, wmin, bottom = O.trace_confidence(conf, cu, w, bottom_percent=25)
+    assert math.isnan(mean[0]) and math.isnan(wmin[0]) and math.isnan(bottom[0])
+    for i, L in enumerate(lens):
+        if L == 0:
+            continue
+        x = [Fraction(int(v * 4), 4) for v in conf[cu[i]:cu[i + 1]]]
+        ww = min(w, L)
+        wins = sorted(sum(x[k:k + ww], Fraction(0)) / ww for k in range(L - ww + 1))
+        m = max(1, -(-len(wins) * 25 // 100))
+        assert Fraction(mean[i]) == sum(x, Fraction(0)) / L or abs(mean[i] - float(sum(x, Fraction(0)) / L)) < 1e-14
+        assert abs(wmin[i] - float(wins[0])) < 1e-14
+        assert abs(bottom[i] - float(sum(wins[:m], Fraction(0)) / m)) < 1e-14
+
+
+def test_trace_confidence_bottom_count_uses_integer_ceiling():
+    # 30 windows at 10 % must take exactly 3 (a float product 0.1*30 rounds above 3)
+    conf = np.arange(30, dtype=np.float64)
+    _, _, bottom = O.trace_confidence(conf, [0, 30], 1)
+    assert bottom[0] == 1.0          # mean of 0, 1, 2
+    _, _, bottom = O.trace_confidence(np.arange(31, dtype=np.float64), [0, 31], 1)
+    assert bottom[0] == 1.5          # ceil(3.1) = 4 -> mean of 0..3
