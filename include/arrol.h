@@ -234,6 +234,37 @@ int arrol_prune_bernoulli(const float* s_norm, const float* uniforms, int32_t N,
                           int32_t* n_survivors, void* stream);
 
 /*
+ * ---- Trace confidence (Sec. 3 "Trace Confidence": the model-intrinsic signal the quality head is compared
+ * with, and the voting weight of the DeepConf-style test-time baseline) ---------------------------------------
+ * Token confidence  H_t = - sum_{j=1..V} log P_t(j)  with P_t = softmax(W h_t)
+ *                       = V * lse_t - <h_t, sum_j W_j>,
+ * lse_t being the logsumexp arrol_logprob already returns, so no second [T, V] product is formed.
+ * hidden, lm_head, T, V, d as in arrol_logprob (d <= 16384); lse fp32 [T] (arrol_logprob's lse_out for the
+ * same hidden and lm_head); conf_out fp32 [T].  A NaN in lse propagates.  T == 0 is a no-op.
+ * workspace: arrol_token_confidence_workspace_bytes(V, d) bytes, 16-byte aligned.
+ */
+size_t arrol_token_confidence_workspace_bytes(int32_t V, int32_t d);
+int arrol_token_confidence(const void* hidden, const void* lm_head, const float* lse, int64_t T,
+                           int32_t V, int32_t d, float* conf_out, void* workspace,
+                           size_t workspace_bytes, void* stream);
+
+/*
+ * Trace-level aggregates of the token confidences (Sec. 3).  Trace i is tokens [cu_seqlens[i],
+ * cu_seqlens[i+1]) of conf (offsets are clamped into [0, T]); with L its length and w = min(window, L):
+ *   mean_out[i]    average token confidence over the trace (the self-uncertainty score),
+ *   windows        H_w = mean of w consecutive tokens, one window per start position (L - w + 1 of them),
+ *   min_out[i]     the smallest window value,
+ *   bottom_out[i]  mean of the lowest max(1, ceil(bottom_percent * n_windows / 100)) window values.
+ * conf fp32 [T]; cu_seqlens int64 [n_seq+1]; outputs fp64 [n_seq], NaN for an empty trace; fp64 arithmetic.
+ * window >= 1, 1 <= bottom_percent <= 100 (the paper's "bottom 10 %" is 10), else ARROL_EINVAL.
+ * workspace: arrol_trace_confidence_workspace_bytes(T, n_seq) bytes, 16-byte aligned.  n_seq == 0 is a no-op.
+ */
+size_t arrol_trace_confidence_workspace_bytes(int64_t T, int32_t n_seq);
+int arrol_trace_confidence(const float* conf, const int64_t* cu_seqlens, int64_t T, int32_t n_seq,
+                           int32_t window, int32_t bottom_percent, double* mean_out, double* min_out,
+                           double* bottom_out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * ---- Training the quality head (Sec. 4.2; Sec. 4.3 (iii); Alg. 1 "optimizer step on policy and quality head") ----
  * The head is fitted on the fly to the rollouts' final rewards with a cross-entropy loss; the hidden states
  * are constants (no gradient reaches the backbone).  For the linear head, with q_i = sigmoid(<w,h_i> + bias):

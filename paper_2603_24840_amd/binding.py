@@ -57,6 +57,10 @@ _SIGNATURES = {
                                              _vp, _sz, _vp]),
     "arrol_logprob_workspace_bytes": (_sz, [_i64, _i32, _i32]),
     "arrol_logprob": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
+    "arrol_token_confidence_workspace_bytes": (_sz, [_i32, _i32]),
+    "arrol_token_confidence": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i32, _i32, _vp, _vp, _sz, _vp]),
+    "arrol_trace_confidence_workspace_bytes": (_sz, [_i64, _i32]),
+    "arrol_trace_confidence": (ctypes.c_int, [_vp, _vp, _i64, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _sz, _vp]),
     "arrol_weighted_vote": (ctypes.c_int, [_vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp]),
     "arrol_histogram": (ctypes.c_int, [_vp, _vp, _i64, _i32, _vp, _vp, _vp]),
     "arrol_calibrate": (ctypes.c_int, [_vp, _vp, _i32, Policy, _vp, _vp, _vp, _vp]),
@@ -309,6 +313,43 @@ def arrol_logprob(hidden, lm_head, targets, out_logprob=None, out_lse=None, want
                              _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
     _check("arrol_logprob", rc)
     return (out_logprob, out_lse) if (want_lse or out_lse is not None) else out_logprob
+
+
+def arrol_token_confidence(hidden, lm_head, lse, workspace=None, stream=None):
+    """hidden bf16 [T, d], lm_head bf16 [V, d], lse fp32 [T] (from arrol_logprob) -> token confidence fp32 [T]."""
+    if hidden.dim() != 2 or lm_head.dim() != 2 or hidden.shape[1] != lm_head.shape[1]:
+        raise ValueError("hidden must be [T, d] and lm_head [V, d]")
+    T, d = hidden.shape
+    V = lm_head.shape[0]
+    if lse.numel() != T:
+        raise ValueError("lse must be [T]")
+    dev = hidden.device
+    if workspace is None:
+        workspace = torch.empty(max(lib().arrol_token_confidence_workspace_bytes(V, d), 16), dtype=torch.uint8, device=dev)
+    conf = torch.empty(T, dtype=torch.float32, device=dev)
+    rc = lib().arrol_token_confidence(_ptr(hidden, torch.bfloat16, "hidden"), _ptr(lm_head, torch.bfloat16, "lm_head"),
+                                      _ptr(lse, torch.float32, "lse"), T, V, d, conf.data_ptr(),
+                                      _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
+    _check("arrol_token_confidence", rc)
+    return conf
+
+
+def arrol_trace_confidence(conf, cu_seqlens, window, bottom_percent=10, workspace=None, stream=None):
+    """conf fp32 [T], cu_seqlens int64 [n+1] -> (trace mean, min window mean, bottom-share window mean) fp64 [n]."""
+    T = conf.numel()
+    n = cu_seqlens.numel() - 1
+    if n < 0:
+        raise ValueError("cu_seqlens must hold at least one offset")
+    dev = conf.device
+    if workspace is None:
+        workspace = torch.empty(max(lib().arrol_trace_confidence_workspace_bytes(T, n), 16), dtype=torch.uint8, device=dev)
+    outs = [torch.empty(n, dtype=torch.float64, device=dev) for _ in range(3)]
+    rc = lib().arrol_trace_confidence(_ptr(conf, torch.float32, "conf"), _ptr(cu_seqlens, torch.int64, "cu_seqlens"),
+                                      T, n, int(window), int(bottom_percent), outs[0].data_ptr(), outs[1].data_ptr(),
+                                      outs[2].data_ptr(), _ptr(workspace, torch.uint8, "workspace"),
+                                      workspace.numel(), _stream(stream))
+    _check("arrol_trace_confidence", rc)
+    return tuple(outs)
 
 
 def arrol_weighted_vote(prob, answer_id, n_questions, C, n_answers, want_tally=False, stream=None):

@@ -30,7 +30,9 @@ def test_header_declares_the_five_stage_calls():
                "arrol_compact_workspace_bytes", "arrol_logprob_workspace_bytes", "arrol_version",
                "arrol_error_string", "arrol_set_tuning", "arrol_histogram", "arrol_calibrate",
                "arrol_prune_bernoulli", "arrol_compact_inplace", "arrol_compact_inplace_workspace_bytes",
-               "arrol_score_mlp", "arrol_score_grad", "arrol_score_grad_workspace_bytes", "arrol_adamw_step"]:
+               "arrol_score_mlp", "arrol_score_grad", "arrol_score_grad_workspace_bytes", "arrol_adamw_step", "arrol_token_confidence",
+               "arrol_token_confidence_workspace_bytes", "arrol_trace_confidence",
+               "arrol_trace_confidence_workspace_bytes"]:
         assert fn in names
 
 
@@ -114,6 +116,22 @@ def test_bad_arguments_are_rejected_on_the_host(pkg):
     assert L.arrol_adamw_step(fake, fake, fake, fake, 8, 1, 1e-3, 1.0, 0.999, 1e-8, 0.0, None, None) == -1
     assert L.arrol_adamw_step(fake, None, fake, fake, 8, 1, 1e-3, 0.9, 0.999, 1e-8, 0.0, None, None) == -1
     assert L.arrol_adamw_step(None, None, None, None, 0, 1, 1e-3, 0.9, 0.999, 1e-8, 0.0, None, None) == 0
+    # trace confidence: bad d / V, null lse, workspace; aggregates: window < 1, percent outside [1, 100]
+    assert L.arrol_token_confidence(fake, fake, fake, 4, 100, 12, fake, fake, 1 << 20, None) == -1
+    assert L.arrol_token_confidence(fake, fake, fake, 4, 0, 16, fake, fake, 1 << 20, None) == -1
+    assert L.arrol_token_confidence(fake, fake, None, 4, 100, 16, fake, fake, 1 << 20, None) == -1
+    assert L.arrol_token_confidence(fake, fake, fake, 4, 100, 16, fake, None, 0, None) == -2
+    assert L.arrol_token_confidence(fake, fake, fake, 4, 100, 16, fake, fake, 64, None) == -2
+    assert L.arrol_token_confidence(None, None, None, 0, 100, 16, None, None, 0, None) == 0
+    assert L.arrol_token_confidence_workspace_bytes(100, 16) >= 2 * 16 * 4
+    assert L.arrol_trace_confidence(fake, fake, 10, 2, 0, 10, fake, fake, fake, fake, 1 << 20, None) == -1
+    assert L.arrol_trace_confidence(fake, fake, 10, 2, 4, 0, fake, fake, fake, fake, 1 << 20, None) == -1
+    assert L.arrol_trace_confidence(fake, fake, 10, 2, 4, 101, fake, fake, fake, fake, 1 << 20, None) == -1
+    assert L.arrol_trace_confidence(fake, None, 10, 2, 4, 10, fake, fake, fake, fake, 1 << 20, None) == -1
+    assert L.arrol_trace_confidence(fake, fake, 10, 2, 4, 10, fake, fake, fake, None, 0, None) == -2
+    assert L.arrol_trace_confidence(fake, fake, 10, 2, 4, 10, fake, fake, fake, fake, 100, None) == -2
+    assert L.arrol_trace_confidence(None, None, 0, 0, 4, 10, None, None, None, None, 0, None) == 0
+    assert L.arrol_trace_confidence_workspace_bytes(10, 2) == 2 * 12 * 8
     # in-place compaction: bad geometry, missing / short workspace
     assert L.arrol_compact_inplace(fake, odd, fake, fake, 4, fake, 32, 16, fake, fake, fake, fake, None, fake, 1 << 20, None) == -1
     assert L.arrol_compact_inplace(fake, lay, fake, fake, 0, fake, 32, 16, fake, fake, fake, fake, None, fake, 1 << 20, None) == -1
