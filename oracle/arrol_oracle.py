@@ -21,6 +21,7 @@ Stages (paper passages in each docstring):
   histogram / calibrate / prune_bernoulli   the practical policy   App. A.4 Eq. 1-2; Alg. 1
   score_mlp, score_ce(_grad), adamw_step    quality head variants and training   Sec. 4.2, 4.3 (iii)
   token_confidence / trace_confidence       trace confidence   Sec. 3
+  grpo_advantage / grpo_objective           group-relative advantage, clipped objective   Sec. 3
 """
 import math
 
@@ -534,3 +535,71 @@ def trace_confidence(conf, cu_seqlens, window, bottom_percent=10):
         m = max(1, (len(vals) * int(bottom_percent) + 99) // 100)
         bottom[i] = math.fsum(vals[:m]) / m
     return mean, wmin, bottom
+
+
+# ----------------------------------------------------------------------------
+# GRPO advantage and clipped-ratio objective (Sec. 3, "Group-Relative Policy Optimization")
+# ----------------------------------------------------------------------------
+def grpo_advantage(reward, group_offsets, ddof=0, eps=0.0):
+    """Group-relative advantage of Sec. 3: A_i = (R_i - mean(R_group)) / std(R_group), over the rollouts of
+    one prompt that are still there after pruning.  Rollouts of group g are [group_offsets[g],
+    group_offsets[g+1]).  std = sqrt(sum (R - mean)^2 / (n - ddof)) (0 when n - ddof <= 0); `eps` is added to
+    it; where std + eps == 0 (all rewards equal, the sparse-signal case the paper describes) A_i = 0.
+    Returns float64 [N]."""
+    r = np.asarray(reward, dtype=np.float32).astype(np.float64)
+    off = np.asarray(group_offsets, dtype=np.int64)
+    adv = np.zeros(r.shape[0], dtype=np.float64)
+    for g in range(off.shape[0] - 1):
+        x = r[off[g]:off[g + 1]]
+        n = x.shape[0]
+        if n == 0:
+            continue
+        mean = math.fsum(x) / n
+        dev = x - mean
+        std = math.sqrt(math.fsum(dev * dev) / (n - ddof)) if n - ddof > 0 else 0.0
+        den = std + float(eps)
+        adv[off[g]:off[g + 1]] = dev / den if den > 0.0 else 0.0
+    return adv
+
+
+def grpo_objective(logp, logp_ref, cu_seqlens, advantage, group_offsets, eps_low=0.2, eps_high=0.2, beta=0.0):
+    """GRPO objective of Sec. 3 on the surviving rollouts:
+        J = mean over groups g of (1/G_g) sum_{i in g} (1/|o_i|) sum_t [ min(r_t A_i, clip(r_t, 1-eps_low,
+            1+eps_high) A_i) - beta * kl_t ],    r_t = exp(logp_t - logp_ref_t)
+    with rollout i = tokens [cu[i], cu[i+1]).  The paper writes the KL term as beta * KL(pi_theta || pi_ref)
+    without an estimator; the per-token estimate used is kl_t = exp(u) - u - 1 with u = logp_ref_t - logp_t
+    (non-negative, and its expectation under pi_theta is the KL divergence).  An empty rollout adds 0.
+    Returns (J, dJ/dlogp float64 [T], number of tokens where the clipped branch is strictly the minimum)."""
+    lp = np.asarray(logp, dtype=np.float32).astype(np.float64)
+    lr = np.asarray(logp_ref, dtype=np.float32).astype(np.float64)
+    cu = np.asarray(cu_seqlens, dtype=np.int64)
+    off = np.asarray(group_offsets, dtype=np.int64)
+    adv = np.asarray(advantage, dtype=np.float32).astype(np.float64)
+    n_groups = off.shape[0] - 1
+    grad = np.zeros(lp.shape[0], dtype=np.float64)
+    n_clipped = 0
+    group_terms = []
+    for g in range(n_groups):
+        G = int(off[g + 1] - off[g])
+        seq_terms = []
+        for i in range(off[g], off[g + 1]):
+            L = int(cu[i + 1] - cu[i])
+            if L == 0:
+                seq_terms.append(0.0)
+                continue
+            tok = []
+            for t in range(cu[i], cu[i + 1]):
+                ratio = math.exp(lp[t] - lr[t])
+                plain = ratio * adv[i]
+                clipped = min(max(ratio, 1.0 - eps_low), 1.0 + eps_high) * adv[i]
+                u = lr[t] - lp[t]
+                kl = math.exp(u) - u - 1.0
+                tok.append(min(plain, clipped) - beta * kl)
+                d = plain if plain <= clipped else 0.0            # d(min)/dlogp: r*A on the unclipped branch
+                d -= beta * (1.0 - math.exp(u))                   # d(kl)/dlogp = 1 - exp(u)
+                grad[t] = d / (L * G * n_groups)
+                n_clipped += 1 if clipped < plain else 0
+            seq_terms.append(math.fsum(tok) / L)
+        group_terms.append(math.fsum(seq_terms) / G if G > 0 else 0.0)
+    J = math.fsum(group_terms) / n_groups if n_groups > 0 else 0.0
+    return J, grad, n_clipped

@@ -828,3 +828,104 @@ def test_trace_confidence_bottom_count_uses_integer_ceiling():
     assert bottom[0] == 1.0          # mean of 0, 1, 2
     _, _, bottom = O.trace_confidence(np.arange(31, dtype=np.float64), [0, 31], 1)
     assert bottom[0] == 1.5          # ceil(3.1) = 4 -> mean of 0..3
+
+
+# ----------------------------------------------------------------------------- GRPO
+def test_grpo_advantage_binary_rewards_closed_form():
+    # k ones among n: A(1) = sqrt((1-p)/p), A(0) = -sqrt(p/(1-p)) with p = k/n (population std)
+    for n, k in [(4, 1), (8, 4), (16, 3), (5, 4)]:
+        r = np.array([1.0] * k + [0.0] * (n - k), dtype=np.float32)
+        adv = O.grpo_advantage(r, [0, n])
+        p = k / n
+        assert np.allclose(adv[:k], math.sqrt((1 - p) / p), rtol=1e-14)
+        assert np.allclose(adv[k:], -math.sqrt(p / (1 - p)), rtol=1e-14)
+
+
+def test_grpo_advantage_is_standardised_per_group_and_zero_for_equal_rewards():
+    rng = np.random.default_rng(31)
+    off = np.array([0, 4, 4, 9, 10, 26])            # an empty group and a singleton among them
+    r = rng.normal(size=26).astype(np.float32)
+    r[4:9] = 0.75                                   # all-equal group
+    adv = O.grpo_advantage(r, off)
+    for g in (0, 4):
+        x = adv[off[g]:off[g + 1]]
+        assert abs(x.mean()) < 1e-14 and abs(np.mean(x * x) - 1.0) < 1e-13
+    assert np.all(adv[4:10] == 0.0)                 # equal rewards and the singleton
+    # sample standard deviation (ddof = 1) rescales by sqrt((n-1)/n); eps enters the denominator
+    a1 = O.grpo_advantage(r, off, ddof=1)
+    assert np.allclose(a1[:4], adv[:4] * math.sqrt(3 / 4), rtol=1e-13)
+    assert a1[9] == 0.0
+    x = r[:4].astype(np.float64)
+    ae = O.grpo_advantage(r, off, eps=0.5)
+    assert np.allclose(ae[:4], (x - x.mean()) / (x.std() + 0.5), rtol=1e-13)
+
+
+def test_grpo_objective_hand_worked_clipping_cases():
+    # one group, four one-token rollouts: (r, A) = (2, 1), (2, -1), (0.5, 1), (0.5, -1), eps = 0.2
+    lp = np.log(np.array([2.0, 2.0, 0.5, 0.5])).astype(np.float32)
+    ratio = np.exp(lp.astype(np.float64))
+    adv = np.array([1.0, -1.0, 1.0, -1.0], dtype=np.float32)
+    J, grad, n_clip = O.grpo_objective(lp, np.zeros(4, dtype=np.float32), [0, 1, 2, 3, 4], adv, [0, 4])
+    terms = [1.2, -ratio[1], ratio[2], -0.8]
+    assert abs(J - sum(terms) / 4) < 1e-15
+    assert n_clip == 2                               # the first and the last
+    assert grad[0] == 0.0 and grad[3] == 0.0
+    assert abs(grad[1] - (-ratio[1]) / 4) < 1e-15 and abs(grad[2] - ratio[2] / 4) < 1e-15
+
+
+def test_grpo_objective_on_policy_is_the_mean_advantage_and_its_gradient():
+    rng = np.random.default_rng(32)
+    lens = [3, 5, 2, 4, 6, 1]
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    off = [0, 2, 6]
+    lp = (-rng.random(cu[-1]) * 3).astype(np.float32)
+    r = rng.normal(size=6).astype(np.float32)
+    adv = O.grpo_advantage(r, off).astype(np.float32)
+    J, grad, n_clip = O.grpo_objective(lp, lp, cu, adv, off, beta=0.3)
+    want = np.mean([adv[0:2].astype(np.float64).mean(), adv[2:6].astype(np.float64).mean()])
+    assert abs(J - want) < 1e-15 and n_clip == 0    # ratio 1 everywhere, KL estimate 0
+    for i, L in enumerate(lens):
+        G = 2 if i < 2 else 4
+        assert np.allclose(grad[cu[i]:cu[i + 1]], float(adv[i]) / (L * G * 2), rtol=1e-14)
+
+
+def test_grpo_objective_gradient_against_central_differences():
+    rng = np.random.default_rng(33)
+    lens = [4, 3, 5, 2]
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    off = [0, 2, 4]
+    T = int(cu[-1])
+    lr = (-rng.random(T) * 2).astype(np.float32)
+    lp = (lr + rng.normal(size=T).astype(np.float32) * 0.3).astype(np.float32)
+    adv = O.grpo_advantage(rng.normal(size=4).astype(np.float32), off).astype(np.float32)
+    args = dict(eps_low=0.2, eps_high=0.28, beta=0.05)
+    J, grad, n_clip = O.grpo_objective(lp, lr, cu, adv, off, **args)
+    assert 0 < n_clip < T                           # both branches occur
+    ratio = np.exp(lp.astype(np.float64) - lr)
+    e = np.float32(2.0 ** -9)
+    for t in range(T):
+        if min(abs(ratio[t] - 0.8), abs(ratio[t] - 1.28)) < 0.01:
+            continue                                # too close to a kink for a finite difference
+        up, dn = lp.copy(), lp.copy()
+        up[t] += e
+        dn[t] -= e
+        fd = (O.grpo_objective(up, lr, cu, adv, off, **args)[0] - O.grpo_objective(dn, lr, cu, adv, off, **args)[0]) \
+            / (float(up[t]) - float(dn[t]))
+        assert abs(fd - grad[t]) < 1e-5 * max(1.0, abs(grad[t]) * 100), (t, fd, grad[t])
+
+
+def test_grpo_kl_estimate_is_nonnegative_and_unbiased_by_enumeration():
+    # E_{x ~ p}[exp(u) - u - 1] with u = log q(x) - log p(x) equals KL(p || q), summed over a small alphabet
+    rng = np.random.default_rng(34)
+    p = rng.random(7); p /= p.sum()
+    q = rng.random(7); q /= q.sum()
+    lp, lq = np.log(p).astype(np.float32), np.log(q).astype(np.float32)
+    # one rollout per symbol, one token each, advantage 0, beta 1: J = -(1/7) sum_x kl(x); weight by p by hand
+    total = 0.0
+    for x in range(7):
+        J, _, _ = O.grpo_objective(lp[x:x + 1], lq[x:x + 1], [0, 1], np.zeros(1, dtype=np.float32), [0, 1], beta=1.0)
+        assert J <= 0.0
+        total += float(np.exp(np.float64(lp[x]))) * (-J)
+    p32, q32 = np.exp(lp.astype(np.float64)), np.exp(lq.astype(np.float64))
+    kl = float(np.sum(p32 * (np.log(p32) - np.log(q32)))) + float(np.sum(q32) - np.sum(p32))
+    assert abs(total - kl) < 1e-12
