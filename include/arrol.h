@@ -265,6 +265,38 @@ int arrol_trace_confidence(const float* conf, const int64_t* cu_seqlens, int64_t
                            double* bottom_out, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * ---- GRPO on the survivors (Sec. 3 "Group-Relative Policy Optimization"; Alg. 1 "advantages") -------------
+ * Group-relative advantage  A_i = (R_i - mean(R_group)) / (std(R_group) + eps)  over the rollouts of one prompt
+ * that survived pruning; rollouts of group g are [group_offsets[g], group_offsets[g+1]) (int64 [n_groups+1],
+ * clamped into [0, N]).  std^2 = sum (R - mean)^2 / (n - ddof), ddof 0 (population) or 1; std = 0 when
+ * n - ddof <= 0; A_i = 0 where std + eps == 0 (all rewards equal).  fp64 arithmetic, fp32 results.
+ * reward fp32 [N]; advantage fp32 [N]; seq_weight NULL or fp32 [N] = 1 / (group size * n_groups), the weight
+ * of rollout i in the objective below.  Rollouts outside every group are not written.
+ */
+int arrol_grpo_advantage(const float* reward, const int64_t* group_offsets, int64_t N, int32_t n_groups,
+                         int32_t ddof, float eps, float* advantage, float* seq_weight, void* stream);
+
+/*
+ * Clipped-ratio objective of Sec. 3 on packed per-token log-probabilities (rollout i = tokens
+ * [cu_seqlens[i], cu_seqlens[i+1])):
+ *   J = sum_i seq_weight_i * (1/|o_i|) * sum_t [ min(r_t A_i, clip(r_t, 1-eps_low, 1+eps_high) A_i) - beta*kl_t ]
+ *   r_t = exp(logp_t - logp_ref_t),  kl_t = exp(u) - u - 1 with u = logp_ref_t - logp_t
+ * (the paper writes beta*KL(pi_theta || pi_ref) without an estimator; kl_t is non-negative and its mean under
+ * pi_theta is that divergence).  With seq_weight from arrol_grpo_advantage this is the mean over groups of the
+ * mean over the group's rollouts of the per-token mean.  An empty rollout adds 0.
+ * logp, logp_ref fp32 [T]; advantage, seq_weight fp32 [n_seq]; objective_out NULL or fp64 [1];
+ * grad_logp NULL or fp32 [T] = dJ/dlogp_t (zero where the clipped branch is the minimum); n_clipped NULL or
+ * int64 [1] = tokens where the clipped branch is strictly smaller.  fp64 arithmetic, fixed summation order.
+ * 0 <= eps_low <= 1, eps_high >= 0, beta >= 0, else ARROL_EINVAL.  n_seq == 0 writes J = 0.
+ * workspace: arrol_grpo_objective_workspace_bytes(n_seq) bytes, 16-byte aligned.
+ */
+size_t arrol_grpo_objective_workspace_bytes(int32_t n_seq);
+int arrol_grpo_objective(const float* logp, const float* logp_ref, const int64_t* cu_seqlens, int64_t T,
+                         int32_t n_seq, const float* advantage, const float* seq_weight, float eps_low,
+                         float eps_high, float beta, double* objective_out, float* grad_logp,
+                         int64_t* n_clipped, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * ---- Training the quality head (Sec. 4.2; Sec. 4.3 (iii); Alg. 1 "optimizer step on policy and quality head") ----
  * The head is fitted on the fly to the rollouts' final rewards with a cross-entropy loss; the hidden states
  * are constants (no gradient reaches the backbone).  For the linear head, with q_i = sigmoid(<w,h_i> + bias):

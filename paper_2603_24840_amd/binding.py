@@ -61,6 +61,10 @@ _SIGNATURES = {
     "arrol_token_confidence": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i32, _i32, _vp, _vp, _sz, _vp]),
     "arrol_trace_confidence_workspace_bytes": (_sz, [_i64, _i32]),
     "arrol_trace_confidence": (ctypes.c_int, [_vp, _vp, _i64, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "arrol_grpo_advantage": (ctypes.c_int, [_vp, _vp, _i64, _i32, _i32, _f32, _vp, _vp, _vp]),
+    "arrol_grpo_objective_workspace_bytes": (_sz, [_i32]),
+    "arrol_grpo_objective": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i32, _vp, _vp, _f32, _f32, _f32, _vp, _vp, _vp,
+                                            _vp, _sz, _vp]),
     "arrol_weighted_vote": (ctypes.c_int, [_vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp]),
     "arrol_histogram": (ctypes.c_int, [_vp, _vp, _i64, _i32, _vp, _vp, _vp]),
     "arrol_calibrate": (ctypes.c_int, [_vp, _vp, _i32, Policy, _vp, _vp, _vp, _vp]),
@@ -350,6 +354,41 @@ def arrol_trace_confidence(conf, cu_seqlens, window, bottom_percent=10, workspac
                                       workspace.numel(), _stream(stream))
     _check("arrol_trace_confidence", rc)
     return tuple(outs)
+
+
+def arrol_grpo_advantage(reward, group_offsets, ddof=0, eps=0.0, stream=None):
+    """reward fp32 [N], group_offsets int64 [n_groups+1] -> (advantage fp32 [N], seq_weight fp32 [N])."""
+    N = reward.numel()
+    n_groups = group_offsets.numel() - 1
+    adv = torch.zeros(N, dtype=torch.float32, device=reward.device)
+    wgt = torch.zeros(N, dtype=torch.float32, device=reward.device)
+    rc = lib().arrol_grpo_advantage(_ptr(reward, torch.float32, "reward"), _ptr(group_offsets, torch.int64, "group_offsets"),
+                                    N, n_groups, int(ddof), float(eps), adv.data_ptr(), wgt.data_ptr(), _stream(stream))
+    _check("arrol_grpo_advantage", rc)
+    return adv, wgt
+
+
+def arrol_grpo_objective(logp, logp_ref, cu_seqlens, advantage, seq_weight, eps_low=0.2, eps_high=0.2, beta=0.0,
+                         want_grad=True, workspace=None, stream=None):
+    """-> (J fp64 [1], dJ/dlogp fp32 [T] or None, n_clipped int64 [1])."""
+    T = logp.numel()
+    n = cu_seqlens.numel() - 1
+    if logp_ref.numel() != T or advantage.numel() != n or seq_weight.numel() != n:
+        raise ValueError("logp/logp_ref must be [T]; advantage/seq_weight [n_seq]")
+    dev = logp.device
+    if workspace is None:
+        workspace = torch.empty(max(lib().arrol_grpo_objective_workspace_bytes(n), 16), dtype=torch.uint8, device=dev)
+    J = torch.empty(1, dtype=torch.float64, device=dev)
+    grad = torch.empty(T, dtype=torch.float32, device=dev) if want_grad else None
+    n_clip = torch.empty(1, dtype=torch.int64, device=dev)
+    rc = lib().arrol_grpo_objective(_ptr(logp, torch.float32, "logp"), _ptr(logp_ref, torch.float32, "logp_ref"),
+                                    _ptr(cu_seqlens, torch.int64, "cu_seqlens"), T, n,
+                                    _ptr(advantage, torch.float32, "advantage"), _ptr(seq_weight, torch.float32, "seq_weight"),
+                                    float(eps_low), float(eps_high), float(beta), J.data_ptr(),
+                                    None if grad is None else grad.data_ptr(), n_clip.data_ptr(),
+                                    _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
+    _check("arrol_grpo_objective", rc)
+    return J, grad, n_clip
 
 
 def arrol_weighted_vote(prob, answer_id, n_questions, C, n_answers, want_tally=False, stream=None):

@@ -32,7 +32,8 @@ def test_header_declares_the_five_stage_calls():
                "arrol_prune_bernoulli", "arrol_compact_inplace", "arrol_compact_inplace_workspace_bytes",
                "arrol_score_mlp", "arrol_score_grad", "arrol_score_grad_workspace_bytes", "arrol_adamw_step", "arrol_token_confidence",
                "arrol_token_confidence_workspace_bytes", "arrol_trace_confidence",
-               "arrol_trace_confidence_workspace_bytes"]:
+               "arrol_trace_confidence_workspace_bytes", "arrol_grpo_advantage", "arrol_grpo_objective",
+               "arrol_grpo_objective_workspace_bytes"]:
         assert fn in names
 
 
@@ -132,6 +133,18 @@ def test_bad_arguments_are_rejected_on_the_host(pkg):
     assert L.arrol_trace_confidence(fake, fake, 10, 2, 4, 10, fake, fake, fake, fake, 100, None) == -2
     assert L.arrol_trace_confidence(None, None, 0, 0, 4, 10, None, None, None, None, 0, None) == 0
     assert L.arrol_trace_confidence_workspace_bytes(10, 2) == 2 * 12 * 8
+    # GRPO: ddof outside {0, 1}, negative eps, clip range / beta outside their domain, workspace
+    assert L.arrol_grpo_advantage(fake, fake, 8, 2, 2, 0.0, fake, None, None) == -1
+    assert L.arrol_grpo_advantage(fake, fake, 8, 2, 0, -1.0, fake, None, None) == -1
+    assert L.arrol_grpo_advantage(fake, None, 8, 2, 0, 0.0, fake, None, None) == -1
+    assert L.arrol_grpo_advantage(None, None, 0, 0, 0, 0.0, None, None, None) == 0
+    assert L.arrol_grpo_objective(fake, fake, fake, 8, 2, fake, fake, 1.5, 0.2, 0.0, fake, None, None, fake, 64, None) == -1
+    assert L.arrol_grpo_objective(fake, fake, fake, 8, 2, fake, fake, 0.2, -0.1, 0.0, fake, None, None, fake, 64, None) == -1
+    assert L.arrol_grpo_objective(fake, fake, fake, 8, 2, fake, fake, 0.2, 0.2, -1.0, fake, None, None, fake, 64, None) == -1
+    assert L.arrol_grpo_objective(fake, fake, fake, 8, 2, None, fake, 0.2, 0.2, 0.0, fake, None, None, fake, 64, None) == -1
+    assert L.arrol_grpo_objective(fake, fake, fake, 8, 2, fake, fake, 0.2, 0.2, 0.0, fake, None, None, None, 0, None) == -2
+    assert L.arrol_grpo_objective(fake, fake, fake, 8, 2, fake, fake, 0.2, 0.2, 0.0, fake, None, None, fake, 16, None) == -2
+    assert L.arrol_grpo_objective_workspace_bytes(2) == 32
     # in-place compaction: bad geometry, missing / short workspace
     assert L.arrol_compact_inplace(fake, odd, fake, fake, 4, fake, 32, 16, fake, fake, fake, fake, None, fake, 1 << 20, None) == -1
     assert L.arrol_compact_inplace(fake, lay, fake, fake, 0, fake, 32, 16, fake, fake, fake, fake, None, fake, 1 << 20, None) == -1
