@@ -7,6 +7,7 @@ HBM before the timed region.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama1b] [--skip-cpu-baseline]
   python bench.py --calibrate-copy      # plain 1 GiB device copy, for scaling rocprof byte counters
+  python bench.py --extras              # adds timings of the calls outside the five-stage step
 """
 import argparse
 import json
@@ -40,6 +41,9 @@ def parse():
     ap.add_argument("--calibrate-copy", action="store_true")
     ap.add_argument("--inplace-compaction", action="store_true",
                     help="also time arrol_compact_inplace on the same pool and survivors (extra JSON object)")
+    ap.add_argument("--extras", action="store_true",
+                    help="also time the entry points outside the five-stage step (stochastic policy, MLP head, head "
+                         "training, trace confidence, GRPO objective) on the same workload (extra JSON object)")
     ap.add_argument("--tune", default="", help="comma list key=value passed to arrol_set_tuning (experiments)")
     ap.add_argument("--only", default="", help="comma list of stages to run (profiling aid); default all")
     return ap.parse_args()
@@ -112,6 +116,79 @@ def cpu_baseline(cfg, t, sample_rows, torch):
                       % (L_s, cfg.n_layers, len(rows), T),
             "stage_seconds_scaled": {k: round(v, 4) for k, v in times.items()},
             "parity_on_sample": {"logprob_max_abs_err": err, "compact_bit_exact": compact_ok}}
+
+
+def time_extras(A, W, cfg, dev, torch, lp_hidden, lm_head, targets, cu, lws, reps=10):
+    """HIP-event timings of the calls that are not part of the five-stage step, at this workload's shapes.
+    Each figure is the mean over `reps` back-to-back calls after two warm-up calls."""
+    def timed(fn):
+        for _ in range(2):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    out = {}
+    N, d, T, V = cfg.n_rollouts, cfg.d, lp_hidden.shape[0], lm_head.shape[0]
+    # stochastic policy (App. A.4): 4096-entry labelled buffer, 128 bins, then one Bernoulli prune of the batch
+    s_buf, label, s_batch, uniforms = W.policy_inputs(cfg, dev)
+    pol = A.Policy(0.5, 0.5, 0.5, 0.05, 0.95, 1.0)
+    c_pos, c_neg = A.arrol_histogram(s_buf, label, 128)
+    q_lut, p_lut, _ = A.arrol_calibrate(c_pos, c_neg, pol)
+    out["histogram"] = {"ms": timed(lambda: A.arrol_histogram(s_buf, label, 128)), "shape": "M=%d, B=128" % s_buf.numel()}
+    out["calibrate"] = {"ms": timed(lambda: A.arrol_calibrate(c_pos, c_neg, pol)), "shape": "B=128, 64 bisection steps"}
+    out["prune_bernoulli"] = {"ms": timed(lambda: A.arrol_prune_bernoulli(s_batch, uniforms, p_lut)),
+                              "shape": "N=%d" % s_batch.numel()}
+    # quality head variants on the batch's checkpoint hidden states
+    hidden, w, bias, labels = W.head_training_inputs(cfg, dev)
+    m = 512
+    g = torch.Generator(device=dev); g.manual_seed(77)
+    w1 = (torch.randn(m, d, generator=g, device=dev) * d ** -0.5).to(torch.bfloat16)
+    b1 = torch.zeros(m, device=dev)
+    w2 = torch.randn(m, generator=g, device=dev) * m ** -0.5
+    ms = timed(lambda: A.arrol_score_mlp(hidden, w1, b1, w2))
+    out["score_mlp"] = {"ms": ms, "shape": "N=%d, d=%d, m=%d" % (N, d, m), "TFLOPs": 2.0 * N * d * m / ms / 1e9}
+    gws = torch.empty(max(16, A.lib().arrol_score_grad_workspace_bytes(N, d)), dtype=torch.uint8, device=dev)
+    ms = timed(lambda: A.arrol_score_grad(hidden, w, bias, labels, workspace=gws))
+    out["score_grad"] = {"ms": ms, "shape": "N=%d, d=%d" % (N, d), "GBps": N * d * 2 / ms / 1e6}
+    _, gw, _ = A.arrol_score_grad(hidden, w, bias, labels, workspace=gws)
+    wt, m1, v1 = w.clone(), torch.zeros_like(w), torch.zeros_like(w)
+    out["adamw_step"] = {"ms": timed(lambda: A.arrol_adamw_step(wt, gw, m1, v1, 1, 1e-3)), "shape": "n=%d" % d}
+    # trace confidence on the survivors' response tokens (lse from the log-prob pass)
+    lp = torch.empty(T, dtype=torch.float32, device=dev)
+    lse = torch.empty(T, dtype=torch.float32, device=dev)
+    A.arrol_logprob(lp_hidden, lm_head, targets, out_logprob=lp, out_lse=lse, workspace=lws)
+    cws = torch.empty(max(16, A.lib().arrol_token_confidence_workspace_bytes(V, d)), dtype=torch.uint8, device=dev)
+    ms = timed(lambda: A.arrol_token_confidence(lp_hidden, lm_head, lse, workspace=cws))
+    by = V * d * 2.0 + T * d * 2.0 + T * 8.0
+    out["token_confidence"] = {"ms": ms, "shape": "T=%d, V=%d, d=%d" % (T, V, d), "GBps": by / ms / 1e6,
+                               "frac_of_hbm_peak": by / ms / 1e6 / HBM_PEAK_GBPS}
+    conf = A.arrol_token_confidence(lp_hidden, lm_head, lse, workspace=cws)
+    cud = cu.to(dev)
+    n_seq = cud.numel() - 1
+    tws = torch.empty(max(16, A.lib().arrol_trace_confidence_workspace_bytes(T, n_seq)), dtype=torch.uint8, device=dev)
+    out["trace_confidence"] = {"ms": timed(lambda: A.arrol_trace_confidence(conf, cud, 2048, 10, workspace=tws)),
+                               "shape": "%d traces, T=%d, window 2048, bottom 10 %%" % (n_seq, T)}
+    # GRPO advantage and objective on the survivors (reference log-probs = current ones plus noise)
+    reward = (torch.rand(n_seq, generator=g, device=dev) < 0.5).to(torch.float32)
+    off = torch.arange(0, n_seq + 1, cfg.K, dtype=torch.int64, device=dev)
+    lp_ref = lp + 0.2 * torch.randn(T, generator=g, device=dev)
+    out["grpo_advantage"] = {"ms": timed(lambda: A.arrol_grpo_advantage(reward, off)),
+                             "shape": "%d groups of %d" % (off.numel() - 1, cfg.K)}
+    adv, wgt = A.arrol_grpo_advantage(reward, off)
+    ows = torch.empty(max(16, A.lib().arrol_grpo_objective_workspace_bytes(n_seq)), dtype=torch.uint8, device=dev)
+    out["grpo_objective"] = {"ms": timed(lambda: A.arrol_grpo_objective(lp, lp_ref, cud, adv, wgt, 0.2, 0.2, 0.01,
+                                                                        workspace=ows)),
+                             "shape": "T=%d, %d rollouts, with gradient" % (T, n_seq)}
+    for v in out.values():
+        for k in list(v):
+            if isinstance(v[k], float):
+                v[k] = round(v[k], 5)
+    return out
 
 
 def main():
@@ -273,6 +350,8 @@ def main():
         result["compact_inplace"] = {"ms": ms, "pages_live": int(iout["n_pages_used"][0]), "pages_moved": moved,
                                      "bytes_read_plus_written": moved_bytes, "GBps": moved_bytes / ms / 1e6,
                                      "frac_of_hbm_peak": moved_bytes / ms / 1e6 / HBM_PEAK_GBPS}
+    if args.extras:
+        result["extras"] = time_extras(A, W, cfg, dev, torch, lp_hidden, lm_head, targets, cu, lws)
     if not args.skip_cpu_baseline and not only:
         tensors = dict(hidden=hidden, w=w, bias=bias, prob=prob, kv_src=kv_src, kv_dst=kv_dst,
                        block_table=block_table, seq_len=seq_len, tokens=tokens, lp_hidden=lp_hidden,

@@ -603,3 +603,41 @@ def grpo_objective(logp, logp_ref, cu_seqlens, advantage, group_offsets, eps_low
         group_terms.append(math.fsum(seq_terms) / G if G > 0 else 0.0)
     J = math.fsum(group_terms) / n_groups if n_groups > 0 else 0.0
     return J, grad, n_clipped
+
+
+# ----------------------------------------------------------------------------
+# training the 2-layer MLP head
+# ----------------------------------------------------------------------------
+def score_mlp_ce_grad(hidden_bits, w1_bits, b1, w2, b2, labels):
+    """Cross-entropy loss of the MLP head of score_mlp (a = relu(W1 h + b1), s = <w2, a> + b2,
+    q = sigmoid(s)) against the rewards, mean over the rows, and its gradient with respect to every head
+    parameter; the hidden states are constants (Sec. 4.2, Sec. 4.3 (iii)).  With r_i = (q_i - y_i)/N:
+        dL/db2 = sum_i r_i                 dL/dw2 = sum_i r_i a_i
+        delta_i = r_i * w2 * [W1 h_i + b1 > 0]
+        dL/db1 = sum_i delta_i             dL/dW1 = sum_i delta_i h_i^T
+    (ReLU's derivative at 0 is taken as 0.)  Returns (loss, gW1 [m, d], gb1 [m], gw2 [m], gb2), float64."""
+    h = bf16_bits_to_f64(hidden_bits)
+    W1 = bf16_bits_to_f64(w1_bits)
+    b1 = np.asarray(b1, dtype=np.float32).astype(np.float64)
+    w2 = np.asarray(w2, dtype=np.float32).astype(np.float64)
+    y = np.asarray(labels, dtype=np.float32).astype(np.float64)
+    n = h.shape[0]
+    m = W1.shape[0]
+    gW1 = np.zeros_like(W1)
+    gb1 = np.zeros(m)
+    gw2 = np.zeros(m)
+    gb2 = 0.0
+    terms = []
+    for i in range(n):
+        pre = W1 @ h[i] + b1
+        act = np.where(pre > 0.0, pre, 0.0)
+        s = math.fsum(act * w2) + float(b2)
+        terms.append(-(y[i] * _log_sigmoid(s) + (1.0 - y[i]) * _log_sigmoid(-s)))
+        q = 1.0 / (1.0 + math.exp(-s)) if s >= 0.0 else math.exp(s) / (1.0 + math.exp(s))
+        r = (q - y[i]) / n
+        delta = np.where(pre > 0.0, r * w2, 0.0)
+        gb2 += r
+        gw2 += r * act
+        gb1 += delta
+        gW1 += np.outer(delta, h[i])
+    return math.fsum(terms) / n, gW1, gb1, gw2, gb2

@@ -929,3 +929,96 @@ def test_grpo_kl_estimate_is_nonnegative_and_unbiased_by_enumeration():
     p32, q32 = np.exp(lp.astype(np.float64)), np.exp(lq.astype(np.float64))
     kl = float(np.sum(p32 * (np.log(p32) - np.log(q32)))) + float(np.sum(q32) - np.sum(p32))
     assert abs(total - kl) < 1e-12
+
+
+# ----------------------------------------------------------------------------- MLP head training
+def _mlp_case(seed, n=12, d=8, m=6):
+    rng = np.random.default_rng(seed)
+    hb = f32_to_bf16_bits(rng.normal(size=(n, d)).astype(np.float32))
+    w1b = f32_to_bf16_bits((rng.normal(size=(m, d)) * 0.5).astype(np.float32))
+    b1 = (rng.normal(size=m) * 0.2).astype(np.float32)
+    w2 = (rng.normal(size=m) * 0.7).astype(np.float32)
+    y = (rng.random(n) < 0.5).astype(np.float32)
+    return hb, w1b, b1, w2, np.float32(0.1), y
+
+
+def _mlp_loss(hb, w1b, b1, w2, b2, y):
+    """Mean cross-entropy through the forward oracle's logits (definition, not the gradient routine)."""
+    s, _ = O.score_mlp(hb, w1b, b1, w2, b2)
+    y = y.astype(np.float64)
+    return float(np.mean(np.maximum(s, 0) - y * s + np.log1p(np.exp(-np.abs(s)))))
+
+
+def test_mlp_grad_loss_is_the_cross_entropy_of_the_forward_oracle():
+    case = _mlp_case(41)
+    loss = O.score_mlp_ce_grad(*case)[0]
+    assert abs(loss - _mlp_loss(*case)) < 1e-13
+
+
+def test_mlp_grad_against_central_differences_of_the_loss():
+    hb, w1b, b1, w2, b2, y = _mlp_case(42)
+    _, gW1, gb1, gw2, gb2 = O.score_mlp_ce_grad(hb, w1b, b1, w2, b2, y)
+    e = 2.0 ** -10
+    # fp32 parameters: perturb by an exactly representable step
+    for u in range(6):
+        for arr, g in ((b1, gb1), (w2, gw2)):
+            up, dn = arr.copy(), arr.copy()
+            up[u] += np.float32(e)
+            dn[u] -= np.float32(e)
+            a_up = (hb, w1b, up, w2, b2, y) if arr is b1 else (hb, w1b, b1, up, b2, y)
+            a_dn = (hb, w1b, dn, w2, b2, y) if arr is b1 else (hb, w1b, b1, dn, b2, y)
+            fd = (_mlp_loss(*a_up) - _mlp_loss(*a_dn)) / (float(up[u]) - float(dn[u]))
+            assert abs(fd - g[u]) < 1e-6, (u, fd, g[u])
+    fd = (_mlp_loss(hb, w1b, b1, w2, np.float32(b2 + e), y) - _mlp_loss(hb, w1b, b1, w2, np.float32(b2 - e), y)) \
+        / (float(np.float32(b2 + e)) - float(np.float32(b2 - e)))
+    assert abs(fd - gb2) < 1e-6
+    # W1 is bf16: step to the neighbouring representable values (one ulp each way)
+    W1 = O.bf16_bits_to_f64(w1b)
+    for (u, c) in [(0, 0), (2, 5), (5, 7), (3, 3)]:
+        up, dn = w1b.copy(), w1b.copy()
+        sign_neg = bool(w1b[u, c] >> 15)
+        up[u, c] = int(w1b[u, c]) + (-1 if sign_neg else 1)
+        dn[u, c] = int(w1b[u, c]) + (1 if sign_neg else -1)
+        step = O.bf16_bits_to_f64(up)[u, c] - O.bf16_bits_to_f64(dn)[u, c]
+        assert step > 0
+        fd = (_mlp_loss(hb, up, b1, w2, b2, y) - _mlp_loss(hb, dn, b1, w2, b2, y)) / step
+        # a one-ulp bf16 step is coarse (2^-8 relative): allow the second-order term, and skip kinks
+        pre_up = O.bf16_bits_to_f64(up) @ O.bf16_bits_to_f64(hb).T + b1[:, None]
+        pre_dn = O.bf16_bits_to_f64(dn) @ O.bf16_bits_to_f64(hb).T + b1[:, None]
+        if np.any((pre_up > 0) != (pre_dn > 0)):
+            continue
+        assert abs(fd - gW1[u, c]) < 2e-3 * max(1e-2, abs(gW1[u, c])), (u, c, fd, gW1[u, c])
+
+
+def test_mlp_grad_reduces_to_the_linear_head_when_every_unit_is_active():
+    # large positive b1 keeps every pre-activation positive: s = <W1^T w2, h> + (<w2, b1> + b2), so the
+    # gradients follow from the linear head's by the chain rule
+    rng = np.random.default_rng(43)
+    n, d, m = 10, 8, 4
+    hb = f32_to_bf16_bits(rng.normal(size=(n, d)).astype(np.float32))
+    w1b = f32_to_bf16_bits((rng.normal(size=(m, d)) * 0.25).astype(np.float32))
+    b1 = np.full(m, 64.0, dtype=np.float32)
+    w2 = np.array([0.5, -0.25, 0.125, -0.5], dtype=np.float32)      # exact in fp32, keeps w_eff representable
+    b2 = np.float32(0.0)
+    y = (rng.random(n) < 0.5).astype(np.float32)
+    W1 = O.bf16_bits_to_f64(w1b)
+    w_eff = W1.T @ w2.astype(np.float64)
+    bias_eff = float(np.dot(w2.astype(np.float64), b1.astype(np.float64)))
+    assert np.all(w_eff.astype(np.float32).astype(np.float64) == w_eff)
+    loss_lin, gw_lin, gb_lin = O.score_ce_grad(hb, w_eff.astype(np.float32), bias_eff, y)
+    loss, gW1, gb1, gw2, gb2 = O.score_mlp_ce_grad(hb, w1b, b1, w2, b2, y)
+    assert abs(loss - loss_lin) < 1e-13
+    assert np.allclose(gW1, np.outer(w2.astype(np.float64), gw_lin), rtol=1e-12, atol=1e-15)
+    assert np.allclose(gb1, w2.astype(np.float64) * gb_lin, rtol=1e-12, atol=1e-15)
+    assert abs(gb2 - gb_lin) < 1e-15
+    # dL/dw2 = sum_i r_i (W1 h_i + b1) = W1 gw_lin + b1 gb_lin
+    assert np.allclose(gw2, W1 @ gw_lin + b1.astype(np.float64) * gb_lin, rtol=1e-12, atol=1e-14)
+
+
+def test_mlp_grad_dead_units_get_no_gradient():
+    hb, w1b, b1, w2, b2, y = _mlp_case(44)
+    b1 = b1.copy()
+    b1[1] = -1000.0                                   # unit 1 never fires
+    _, gW1, gb1, gw2, _ = O.score_mlp_ce_grad(hb, w1b, b1, w2, b2, y)
+    assert np.all(gW1[1] == 0.0) and gb1[1] == 0.0 and gw2[1] == 0.0
+    assert np.any(gW1[0] != 0.0)
