@@ -152,6 +152,9 @@ def time_extras(A, W, cfg, dev, torch, lp_hidden, lm_head, targets, cu, lws, rep
     w2 = torch.randn(m, generator=g, device=dev) * m ** -0.5
     ms = timed(lambda: A.arrol_score_mlp(hidden, w1, b1, w2))
     out["score_mlp"] = {"ms": ms, "shape": "N=%d, d=%d, m=%d" % (N, d, m), "TFLOPs": 2.0 * N * d * m / ms / 1e9}
+    mws = torch.empty(max(256, A.lib().arrol_score_mlp_grad_workspace_bytes(N, d, m)), dtype=torch.uint8, device=dev)
+    ms = timed(lambda: A.arrol_score_mlp_grad(hidden, w1, b1, w2, 0.0, labels, workspace=mws))
+    out["score_mlp_grad"] = {"ms": ms, "shape": "N=%d, d=%d, m=%d" % (N, d, m), "TFLOPs": 6.0 * N * d * m / ms / 1e9}
     gws = torch.empty(max(16, A.lib().arrol_score_grad_workspace_bytes(N, d)), dtype=torch.uint8, device=dev)
     ms = timed(lambda: A.arrol_score_grad(hidden, w, bias, labels, workspace=gws))
     out["score_grad"] = {"ms": ms, "shape": "N=%d, d=%d" % (N, d), "GBps": N * d * 2 / ms / 1e6}

@@ -316,6 +316,24 @@ int arrol_score_grad(const void* hidden, int64_t row_stride_elems, const int64_t
                      size_t workspace_bytes, void* stream);
 
 /*
+ * The same loss for the MLP head of arrol_score_mlp (a = relu(W1 h + b1), s = <w2,a> + b2), with the
+ * gradient of every head parameter.  With r_i = (q_i - y_i)/N and delta_i = r_i * w2 * [W1 h_i + b1 > 0]:
+ *   dL/db2 = sum_i r_i,  dL/dw2 = sum_i r_i a_i,  dL/db1 = sum_i delta_i,  dL/dW1 = sum_i delta_i h_i^T
+ * hidden, row_stride_elems, row_index, w1, b1, w2, b2, n_rows, d, m as in arrol_score_mlp; labels fp32 [n_rows].
+ * loss_out NULL or fp32 [1]; grad_w1 fp32 [m, d]; grad_b1, grad_w2 fp32 [m]; grad_b2 NULL or fp32 [1].
+ * The pre-activations are recomputed on the matrix cores; delta is rounded to bf16 before the contraction
+ * over the rollouts (bf16 products, fp32 accumulation), everything else is fp32; sums in a fixed order.
+ * n_rows == 0 writes zeros.
+ * workspace: arrol_score_mlp_grad_workspace_bytes(n_rows, d, m) bytes, 256-byte aligned, caller-owned.
+ */
+size_t arrol_score_mlp_grad_workspace_bytes(int32_t n_rows, int32_t d, int32_t m);
+int arrol_score_mlp_grad(const void* hidden, int64_t row_stride_elems, const int64_t* row_index,
+                         const void* w1, const float* b1, const float* w2, float b2, const float* labels,
+                         int32_t n_rows, int32_t d, int32_t m, float* loss_out, float* grad_w1,
+                         float* grad_b1, float* grad_w2, float* grad_b2, void* workspace,
+                         size_t workspace_bytes, void* stream);
+
+/*
  * One AdamW update in place (the paper names no optimizer; AdamW with decoupled weight decay is this
  * build's reading).  With t = step >= 1:
  *   m <- beta1 m + (1-beta1) g;  v <- beta2 v + (1-beta2) g^2

@@ -47,6 +47,9 @@ _SIGNATURES = {
     "arrol_score_mlp": (ctypes.c_int, [_vp, _i64, _vp, _vp, _vp, _vp, _f32, _i32, _i32, _i32, _vp, _vp, _vp]),
     "arrol_score_grad_workspace_bytes": (_sz, [_i32, _i32]),
     "arrol_score_grad": (ctypes.c_int, [_vp, _i64, _vp, _vp, _f32, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "arrol_score_mlp_grad_workspace_bytes": (_sz, [_i32, _i32, _i32]),
+    "arrol_score_mlp_grad": (ctypes.c_int, [_vp, _i64, _vp, _vp, _vp, _vp, _f32, _vp, _i32, _i32, _i32, _vp, _vp, _vp,
+                                            _vp, _vp, _vp, _sz, _vp]),
     "arrol_adamw_step": (ctypes.c_int, [_vp, _vp, _vp, _vp, _i64, _i32, _f32, _f32, _f32, _f32, _f32, _vp, _vp]),
     "arrol_select": (ctypes.c_int, [_vp, _i32, _i32, _i32, _f32, _vp, _vp, _vp]),
     "arrol_compact_workspace_bytes": (_sz, [_i32]),
@@ -190,6 +193,35 @@ def arrol_score_grad(hidden, w, bias, labels, row_index=None, workspace=None, st
                                 _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
     _check("arrol_score_grad", rc)
     return loss, grad_w, grad_b
+
+
+def arrol_score_mlp_grad(hidden, w1, b1, w2, b2, labels, row_index=None, workspace=None, stream=None):
+    """Cross-entropy loss of the MLP head and its gradients: -> dict(loss [1], grad_w1 [m, d], grad_b1 [m],
+    grad_w2 [m], grad_b2 [1]), all fp32."""
+    if hidden.dim() != 2 or hidden.dtype != torch.bfloat16 or not hidden.is_cuda or hidden.stride(1) != 1:
+        raise TypeError("hidden must be a 2-D bf16 GPU tensor with contiguous rows")
+    d = hidden.shape[1]
+    m = w1.shape[0]
+    n = hidden.shape[0] if row_index is None else row_index.numel()
+    if w1.shape[1] != d or w2.numel() != m or (b1 is not None and b1.numel() != m) or labels.numel() != n:
+        raise ValueError("w1 must be [m, d], b1 and w2 [m], labels [n]")
+    dev = hidden.device
+    if workspace is None:
+        workspace = torch.empty(max(lib().arrol_score_mlp_grad_workspace_bytes(n, d, m), 256), dtype=torch.uint8, device=dev)
+    out = dict(loss=torch.empty(1, dtype=torch.float32, device=dev),
+               grad_w1=torch.empty((m, d), dtype=torch.float32, device=dev),
+               grad_b1=torch.empty(m, dtype=torch.float32, device=dev),
+               grad_w2=torch.empty(m, dtype=torch.float32, device=dev),
+               grad_b2=torch.empty(1, dtype=torch.float32, device=dev))
+    row_stride = hidden.stride(0) if hidden.shape[0] > 1 else max(d, hidden.stride(0))
+    rc = lib().arrol_score_mlp_grad(hidden.data_ptr(), row_stride, _ptr(row_index, torch.int64, "row_index"),
+                                    _ptr(w1, torch.bfloat16, "w1"), _ptr(b1, torch.float32, "b1"),
+                                    _ptr(w2, torch.float32, "w2"), float(b2), _ptr(labels, torch.float32, "labels"),
+                                    n, d, m, out["loss"].data_ptr(), out["grad_w1"].data_ptr(),
+                                    out["grad_b1"].data_ptr(), out["grad_w2"].data_ptr(), out["grad_b2"].data_ptr(),
+                                    _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
+    _check("arrol_score_mlp_grad", rc)
+    return out
 
 
 def arrol_adamw_step(param, grad, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0,

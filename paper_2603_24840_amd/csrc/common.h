@@ -60,3 +60,33 @@ __device__ __forceinline__ float wave_sum_f32(float v) {
 }
 __device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
+// fp32 -> bf16, round to nearest even (NaN stays a quiet NaN)
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return static_cast<uint16_t>(u >> 16);
+}
+
+// out[c] = scale * sum_p partial[p*stride + c] for c < width, partials added in index order within each of
+// eight interleaved groups and the groups in order: bit-reproducible.  n_partials == 0 writes zeros.
+// Launch with (width + 31) / 32 workgroups of 256.
+template <int kUnused = 0>
+__global__ __launch_bounds__(256) void reduce_rows_f32_kernel(const float* __restrict__ partial, int n_partials,
+                                                              int64_t stride, int64_t width, float scale,
+                                                              float* __restrict__ out) {
+    __shared__ float red[8][32];
+    const int cx = threadIdx.x & 31, ry = threadIdx.x >> 5;
+    const int64_t col = static_cast<int64_t>(blockIdx.x) * 32 + cx;
+    float s = 0.f;
+    if (col < width)
+        for (int p = ry; p < n_partials; p += 8) s += partial[static_cast<int64_t>(p) * stride + col];
+    red[ry][cx] = s;
+    __syncthreads();
+    if (ry == 0 && col < width) {
+        float t = 0.f;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) t += red[k][cx];
+        out[col] = t * scale;
+    }
+}

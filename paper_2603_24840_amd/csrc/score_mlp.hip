@@ -6,6 +6,14 @@
 // on the accumulators in registers; the [N, m] activations never reach memory.
 // Tile: 256 hidden units x 128 rollouts per workgroup pass, 4 wavefronts, each 2 x (32 units) x 128
 // rollouts; K chunks of 64 staged global -> registers -> LDS (two stages, XOR-swizzled 16-byte chunks).
+//
+// arrol_score_mlp_grad: cross-entropy training gradient of the same head (Sec. 4.2, Sec. 4.3 (iii)).  The same
+// tile loop runs in two more modes:
+//   delta   recomputes the pre-activations and, instead of the w2 dot, writes delta^T[u][i] =
+//           r_i * w2[u] * [pre > 0] (bf16, unit-major) and the per-workgroup sums for dL/dw2 and dL/db1;
+//   wgrad   the contraction over rollouts dL/dW1 = delta^T . H as the same "A rows x B rows over a shared
+//           contiguous K" product, with A = delta^T [m, N] and B = H^T [d, N] (transposed once into the
+//           workspace), fp32 tile stores, optionally split over K with partial slabs added in a fixed order.
 #include "common.h"
 
 namespace {
@@ -26,13 +34,27 @@ constexpr int kPassB = BR * (BK / 8) / kThreads;
 
 __device__ __forceinline__ int chunk_offset(int r, int c) { return r * 128 + ((c ^ ((r >> 1) & 7)) << 4); }
 
+enum MlpMode { kForward = 0, kDelta = 1, kWgrad = 2 };
+
+// The tile loop multiplies A rows (w1, a_stride elements apart, m of them) with B rows (hidden, n_rows of
+// them) over a contiguous K extent of d elements.
 struct MlpArgs {
     const uint16_t* hidden; int64_t row_stride; const int64_t* row_index;
-    const uint16_t* w1; const float* b1; const float* w2; float b2;
+    const uint16_t* w1; int64_t a_stride; const float* b1; const float* w2; float b2;
     int n_rows, d, m;
     float* score_out; float* prob_out;
+    // delta mode
+    const float* resid;          // [n_rows] r_i = (q_i - y_i) / N
+    uint16_t* delta_t;           // [m][delta_stride] bf16
+    int64_t delta_stride;
+    float* unit_partial;         // [gridDim.x][2][m]: sums over the workgroup's rollouts for dL/dw2, dL/db1
+    // wgrad mode: blockIdx.y = K split, blockIdx.z = group of 256 A rows
+    float* c_out;                // [gridDim.y][m][c_stride] fp32
+    int64_t c_stride;
+    int kc_per_split;            // K chunks (of 64) per split
 };
 
+template <int MODE>
 __global__ __launch_bounds__(kThreads) void score_mlp_kernel(MlpArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -50,20 +72,34 @@ __global__ __launch_bounds__(kThreads) void score_mlp_kernel(MlpArgs a) {
         const int64_t src = a.row_index ? a.row_index[r] : r;
         h_row[p] = a.hidden + src * a.row_stride;
     }
-    const int n_kc = (a.d + BK - 1) / BK;
-    const int n_groups = (a.m + BU - 1) / BU;
+    const int n_kc_all = (a.d + BK - 1) / BK;
+    // forward / delta: every K chunk, every group of 256 units in turn; wgrad: one K split, one group
+    const int kc0 = MODE == kWgrad ? static_cast<int>(blockIdx.y) * a.kc_per_split : 0;
+    const int kc1 = MODE == kWgrad ? (kc0 + a.kc_per_split < n_kc_all ? kc0 + a.kc_per_split : n_kc_all) : n_kc_all;
+    const int n_kc = kc1 - kc0;
+    const int g0 = MODE == kWgrad ? static_cast<int>(blockIdx.z) : 0;
+    const int n_groups = MODE == kWgrad ? 1 : (a.m + BU - 1) / BU;
     const int total_it = n_groups * n_kc;
 
+    float resid[TR] = {0.f, 0.f, 0.f, 0.f};
+    if (MODE == kDelta) {
+#pragma unroll
+        for (int j = 0; j < TR; ++j) {
+            const int r = row0 + j * 32 + l31;
+            resid[j] = r < a.n_rows ? a.resid[r] : 0.f;
+        }
+    }
+
     uint4 stage[kPassA + kPassB];
-    int ld_g = 0, ld_kc = 0;
+    int ld_g = g0, ld_kc = 0;
     auto issue_loads = [&]() {
-        const int k = ld_kc * BK + ld_c * 8;
+        const int k = (kc0 + ld_kc) * BK + ld_c * 8;
         const bool k_ok = k < a.d;
 #pragma unroll
         for (int p = 0; p < kPassA; ++p) {
             int u = ld_g * BU + ld_r + p * 32;
             u = u < a.m ? u : a.m - 1;
-            stage[p] = k_ok ? *reinterpret_cast<const uint4*>(a.w1 + static_cast<int64_t>(u) * a.d + k) : make_uint4(0, 0, 0, 0);
+            stage[p] = k_ok ? *reinterpret_cast<const uint4*>(a.w1 + static_cast<int64_t>(u) * a.a_stride + k) : make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
         for (int p = 0; p < kPassB; ++p)
@@ -92,7 +128,7 @@ __global__ __launch_bounds__(kThreads) void score_mlp_kernel(MlpArgs a) {
     issue_loads();
     store_stage(0);
     __syncthreads();
-    int g = 0, kc = 0;
+    int g = g0, kc = 0;
     for (int it = 0; it < total_it; ++it) {
         const bool more = it + 1 < total_it;
         if (more) issue_loads();
@@ -117,25 +153,62 @@ __global__ __launch_bounds__(kThreads) void score_mlp_kernel(MlpArgs a) {
         if (more) store_stage((it + 1) & 1);
         __syncthreads();
         if (++kc == n_kc) {
-            // acc[c][j][v] = pre-activation of unit g*BU + c*128 + wave*32 + (v/4)*8 + lh*4 + v%4
+            // acc[c][j][v] belongs to A row (unit) g*BU + c*128 + wave*32 + (v/4)*8 + lh*4 + v%4 and B row
+            // (rollout) row0 + j*32 + l31
 #pragma unroll
             for (int c = 0; c < TU; ++c)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int u = g * BU + c * 128 + wave * 32 + (v >> 2) * 8 + lh * 4 + (v & 3);
                     const bool live = u < a.m;
-                    const float bias = (live && a.b1) ? a.b1[u] : 0.f;
-                    const float w = live ? a.w2[u] : 0.f;
+                    if (MODE == kWgrad) {
+                        float* crow = a.c_out + (static_cast<int64_t>(blockIdx.y) * a.m + u) * a.c_stride;
 #pragma unroll
-                    for (int j = 0; j < TR; ++j) {
-                        part[j] = fmaf(fmaxf(acc[c][j][v] + bias, 0.f), w, part[j]);
-                        acc[c][j][v] = 0.f;
+                        for (int j = 0; j < TR; ++j) {
+                            const int col = row0 + j * 32 + l31;
+                            if (live && col < a.n_rows) crow[col] = acc[c][j][v];
+                            acc[c][j][v] = 0.f;
+                        }
+                    } else {
+                        const float bias = (live && a.b1) ? a.b1[u] : 0.f;
+                        const float w = live ? a.w2[u] : 0.f;
+                        if (MODE == kForward) {
+#pragma unroll
+                            for (int j = 0; j < TR; ++j) {
+                                part[j] = fmaf(fmaxf(acc[c][j][v] + bias, 0.f), w, part[j]);
+                                acc[c][j][v] = 0.f;
+                            }
+                        } else {
+                            float gw = 0.f, gb = 0.f;
+                            uint16_t* drow = a.delta_t + static_cast<int64_t>(live ? u : 0) * a.delta_stride + row0 + l31;
+#pragma unroll
+                            for (int j = 0; j < TR; ++j) {
+                                const float pre = acc[c][j][v] + bias;
+                                const float dl = pre > 0.f ? resid[j] * w : 0.f;
+                                gw = fmaf(resid[j], fmaxf(pre, 0.f), gw);
+                                gb += dl;
+                                if (live) drow[j * 32] = f32_to_bf16_rne(dl);
+                                acc[c][j][v] = 0.f;
+                            }
+                            // sum over the 32 rollout lanes of this half-wave (both halves run the same steps)
+#pragma unroll
+                            for (int msk = 16; msk >= 1; msk >>= 1) {
+                                gw += __shfl_xor(gw, msk, ARROL_WAVE);
+                                gb += __shfl_xor(gb, msk, ARROL_WAVE);
+                            }
+                            if (live && l31 == 0) {
+                                float* up = a.unit_partial + static_cast<int64_t>(blockIdx.x) * 2 * a.m;
+                                up[u] = gw;
+                                up[a.m + u] = gb;
+                            }
+                        }
                     }
                 }
             kc = 0;
             ++g;
         }
     }
+    if (MODE != kForward) return;
     // lane halves hold different units of the same rollout; then the four waves
 #pragma unroll
     for (int j = 0; j < TR; ++j) part[j] += __shfl_xor(part[j], 32, ARROL_WAVE);
@@ -159,6 +232,100 @@ __global__ __launch_bounds__(kThreads) void score_mlp_kernel(MlpArgs a) {
     }
 }
 
+// r_i = (q_i - y_i) / N and the loss, one workgroup, fixed summation order
+__global__ __launch_bounds__(1024) void mlp_residual_kernel(const float* __restrict__ score,
+                                                            const float* __restrict__ prob,
+                                                            const float* __restrict__ labels, int n_rows,
+                                                            float* __restrict__ resid, float* __restrict__ loss_out,
+                                                            float* __restrict__ grad_b2) {
+    __shared__ float red[2][16];
+    const float inv_n = 1.f / static_cast<float>(n_rows);
+    float loss = 0.f, rs = 0.f;
+    for (int i = threadIdx.x; i < n_rows; i += 1024) {
+        const float s = score[i], y = labels[i];
+        const float r = (prob[i] - y) * inv_n;
+        resid[i] = r;
+        rs += r;
+        loss += fmaxf(s, 0.f) - y * s + log1pf(expf(-fabsf(s)));
+    }
+    loss = wave_sum_f32(loss);
+    rs = wave_sum_f32(rs);
+    const int lane = threadIdx.x & (ARROL_WAVE - 1), wave = threadIdx.x / ARROL_WAVE;
+    if (lane == 0) { red[0][wave] = loss; red[1][wave] = rs; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float a = 0.f, b = 0.f;
+        for (int w = 0; w < 16; ++w) { a += red[0][w]; b += red[1][w]; }
+        if (loss_out) *loss_out = a * inv_n;
+        if (grad_b2) *grad_b2 = b;
+    }
+}
+
+// out[c][i] = hidden[row(i)][c] for i < n_rows, 0 for n_rows <= i < n_pad: 64 x 64 tiles through LDS
+__global__ __launch_bounds__(256) void mlp_transpose_kernel(const uint16_t* __restrict__ hidden, int64_t row_stride,
+                                                            const int64_t* __restrict__ row_index, int n_rows,
+                                                            int d, int n_pad, uint16_t* __restrict__ out) {
+    __shared__ uint16_t tile[64][66];
+    const int i0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int r = ty; r < 64; r += 4) {
+        const int i = i0 + r, c = c0 + tx;
+        uint16_t v = 0;
+        if (i < n_rows && c < d) {
+            const int64_t src = row_index ? row_index[i] : i;
+            v = hidden[src * row_stride + c];
+        }
+        tile[r][tx] = v;
+    }
+    __syncthreads();
+    for (int r = ty; r < 64; r += 4) {
+        const int c = c0 + r, i = i0 + tx;
+        if (c < d && i < n_pad) out[static_cast<int64_t>(c) * n_pad + i] = tile[tx][r];
+    }
+}
+
+struct GradPlan {
+    int n_rb, n_pad, n_cb, n_groups, n_kc, splits, kc_per_split;
+    size_t off_score, off_prob, off_resid, off_ht, off_dt, off_unit, off_slab, total;
+};
+
+size_t align256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
+
+GradPlan make_grad_plan(int n_rows, int d, int m) {
+    GradPlan p;
+    p.n_rb = (n_rows + BR - 1) / BR;
+    p.n_pad = p.n_rb * BR;
+    p.n_cb = (d + BR - 1) / BR;              // wgrad: 128 columns of dL/dW1 per workgroup
+    p.n_groups = (m + BU - 1) / BU;
+    p.n_kc = p.n_pad / BK;
+    // split K so that about 256 workgroups run, each with at least 8 chunks; at most 8 partial slabs
+    int s = 256 / (p.n_cb * p.n_groups);
+    if (s > p.n_kc / 8) s = p.n_kc / 8;
+    if (s > 8) s = 8;
+    if (s < 1) s = 1;
+    p.kc_per_split = (p.n_kc + s - 1) / s;
+    p.splits = (p.n_kc + p.kc_per_split - 1) / p.kc_per_split;
+    size_t o = 0;
+    p.off_score = o; o = align256(o + sizeof(float) * n_rows);
+    p.off_prob = o;  o = align256(o + sizeof(float) * n_rows);
+    p.off_resid = o; o = align256(o + sizeof(float) * n_rows);
+    p.off_ht = o;    o = align256(o + sizeof(uint16_t) * static_cast<size_t>(d) * p.n_pad);
+    p.off_dt = o;    o = align256(o + sizeof(uint16_t) * static_cast<size_t>(m) * p.n_pad);
+    p.off_unit = o;  o = align256(o + sizeof(float) * static_cast<size_t>(p.n_rb) * 2 * m);
+    p.off_slab = o;
+    if (p.splits > 1) o = align256(o + sizeof(float) * static_cast<size_t>(p.splits) * m * d);
+    p.total = o;
+    return p;
+}
+
+template <int MODE>
+int launch_mlp(const MlpArgs& a, dim3 grid, hipStream_t st) {
+    static bool lds_ok[64] = {};
+    if (!arrol_allow_lds(&score_mlp_kernel<MODE>, kLdsBytes, lds_ok)) return ARROL_EHIP;
+    hipLaunchKernelGGL(score_mlp_kernel<MODE>, grid, dim3(kThreads), kLdsBytes, st, a);
+    return arrol_launch_status();
+}
+
 }  // namespace
 
 extern "C" int arrol_score_mlp(const void* hidden, int64_t row_stride_elems, const int64_t* row_index,
@@ -167,13 +334,82 @@ extern "C" int arrol_score_mlp(const void* hidden, int64_t row_stride_elems, con
     if (n_rows < 0 || d < 8 || (d & 7) || m < 1 || row_stride_elems < d || (row_stride_elems & 7)) return ARROL_EINVAL;
     if (n_rows == 0) return ARROL_OK;
     if (!hidden || !w1 || !w2 || !prob_out || !arrol_aligned16(hidden) || !arrol_aligned16(w1)) return ARROL_EINVAL;
-    static bool lds_ok[64] = {};
-    if (!arrol_allow_lds(&score_mlp_kernel, kLdsBytes, lds_ok)) return ARROL_EHIP;
-    MlpArgs a;
+    MlpArgs a = {};
     a.hidden = static_cast<const uint16_t*>(hidden); a.row_stride = row_stride_elems; a.row_index = row_index;
-    a.w1 = static_cast<const uint16_t*>(w1); a.b1 = b1; a.w2 = w2; a.b2 = b2;
+    a.w1 = static_cast<const uint16_t*>(w1); a.a_stride = d; a.b1 = b1; a.w2 = w2; a.b2 = b2;
     a.n_rows = n_rows; a.d = d; a.m = m; a.score_out = score_out; a.prob_out = prob_out;
-    hipLaunchKernelGGL(score_mlp_kernel, dim3((n_rows + BR - 1) / BR), dim3(kThreads), kLdsBytes,
-                       static_cast<hipStream_t>(stream), a);
+    return launch_mlp<kForward>(a, dim3((n_rows + BR - 1) / BR), static_cast<hipStream_t>(stream));
+}
+
+extern "C" size_t arrol_score_mlp_grad_workspace_bytes(int32_t n_rows, int32_t d, int32_t m) {
+    if (n_rows < 1 || d < 8 || m < 1) return 0;
+    return make_grad_plan(n_rows, d, m).total;
+}
+
+extern "C" int arrol_score_mlp_grad(const void* hidden, int64_t row_stride_elems, const int64_t* row_index,
+                                    const void* w1, const float* b1, const float* w2, float b2,
+                                    const float* labels, int32_t n_rows, int32_t d, int32_t m, float* loss_out,
+                                    float* grad_w1, float* grad_b1, float* grad_w2, float* grad_b2,
+                                    void* workspace, size_t workspace_bytes, void* stream) {
+    if (n_rows < 0 || d < 8 || (d & 7) || m < 1 || row_stride_elems < d || (row_stride_elems & 7)) return ARROL_EINVAL;
+    if (!grad_w1 || !grad_b1 || !grad_w2) return ARROL_EINVAL;
+    if (n_rows == 0) {   // empty batch: zero loss and gradients
+        hipStream_t s0 = static_cast<hipStream_t>(stream);
+        const int64_t width = static_cast<int64_t>(m) * d;
+        hipLaunchKernelGGL(reduce_rows_f32_kernel<0>, dim3(static_cast<unsigned>((width + 31) / 32)), dim3(256), 0, s0,
+                           nullptr, 0, width, width, 0.f, grad_w1);
+        hipLaunchKernelGGL(reduce_rows_f32_kernel<0>, dim3((m + 31) / 32), dim3(256), 0, s0, nullptr, 0,
+                           static_cast<int64_t>(m), static_cast<int64_t>(m), 0.f, grad_b1);
+        hipLaunchKernelGGL(reduce_rows_f32_kernel<0>, dim3((m + 31) / 32), dim3(256), 0, s0, nullptr, 0,
+                           static_cast<int64_t>(m), static_cast<int64_t>(m), 0.f, grad_w2);
+        if (loss_out) hipLaunchKernelGGL(reduce_rows_f32_kernel<0>, dim3(1), dim3(256), 0, s0, nullptr, 0, 1, 1, 0.f, loss_out);
+        if (grad_b2) hipLaunchKernelGGL(reduce_rows_f32_kernel<0>, dim3(1), dim3(256), 0, s0, nullptr, 0, 1, 1, 0.f, grad_b2);
+        return arrol_launch_status();
+    }
+    if (!hidden || !w1 || !w2 || !labels || !arrol_aligned16(hidden) || !arrol_aligned16(w1)) return ARROL_EINVAL;
+    const GradPlan p = make_grad_plan(n_rows, d, m);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < p.total) return ARROL_EWORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    float* score = reinterpret_cast<float*>(ws + p.off_score);
+    float* prob = reinterpret_cast<float*>(ws + p.off_prob);
+    float* resid = reinterpret_cast<float*>(ws + p.off_resid);
+    uint16_t* ht = reinterpret_cast<uint16_t*>(ws + p.off_ht);
+    uint16_t* dt = reinterpret_cast<uint16_t*>(ws + p.off_dt);
+    float* unit = reinterpret_cast<float*>(ws + p.off_unit);
+    float* slab = reinterpret_cast<float*>(ws + p.off_slab);
+
+    // forward pass, residuals and loss
+    MlpArgs a = {};
+    a.hidden = static_cast<const uint16_t*>(hidden); a.row_stride = row_stride_elems; a.row_index = row_index;
+    a.w1 = static_cast<const uint16_t*>(w1); a.a_stride = d; a.b1 = b1; a.w2 = w2; a.b2 = b2;
+    a.n_rows = n_rows; a.d = d; a.m = m; a.score_out = score; a.prob_out = prob;
+    int rc = launch_mlp<kForward>(a, dim3(p.n_rb), st);
+    if (rc != ARROL_OK) return rc;
+    hipLaunchKernelGGL(mlp_residual_kernel, dim3(1), dim3(1024), 0, st, score, prob, labels, n_rows, resid, loss_out,
+                       grad_b2);
+    // delta^T and the per-unit sums
+    a.resid = resid; a.delta_t = dt; a.delta_stride = p.n_pad; a.unit_partial = unit;
+    rc = launch_mlp<kDelta>(a, dim3(p.n_rb), st);
+    if (rc != ARROL_OK) return rc;
+    hipLaunchKernelGGL(reduce_rows_f32_kernel<0>, dim3((m + 31) / 32), dim3(256), 0, st, unit, p.n_rb,
+                       static_cast<int64_t>(2) * m, static_cast<int64_t>(m), 1.f, grad_w2);
+    hipLaunchKernelGGL(reduce_rows_f32_kernel<0>, dim3((m + 31) / 32), dim3(256), 0, st, unit + m, p.n_rb,
+                       static_cast<int64_t>(2) * m, static_cast<int64_t>(m), 1.f, grad_b1);
+    // H^T, then dL/dW1 = delta^T . H over the rollouts
+    hipLaunchKernelGGL(mlp_transpose_kernel, dim3(p.n_pad / 64, (d + 63) / 64), dim3(256), 0, st,
+                       static_cast<const uint16_t*>(hidden), row_stride_elems, row_index, n_rows, d, p.n_pad, ht);
+    MlpArgs g = {};
+    g.hidden = ht; g.row_stride = p.n_pad; g.row_index = nullptr;
+    g.w1 = dt; g.a_stride = p.n_pad;
+    g.n_rows = d; g.d = p.n_pad; g.m = m;
+    g.c_out = p.splits > 1 ? slab : grad_w1; g.c_stride = d; g.kc_per_split = p.kc_per_split;
+    rc = launch_mlp<kWgrad>(g, dim3(p.n_cb, p.splits, p.n_groups), st);
+    if (rc != ARROL_OK) return rc;
+    if (p.splits > 1) {
+        const int64_t width = static_cast<int64_t>(m) * d;
+        hipLaunchKernelGGL(reduce_rows_f32_kernel<0>, dim3(static_cast<unsigned>((width + 31) / 32)), dim3(256), 0, st,
+                           slab, p.splits, width, width, 1.f, grad_w1);
+    }
     return arrol_launch_status();
 }

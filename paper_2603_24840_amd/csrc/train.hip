@@ -137,13 +137,6 @@ __global__ __launch_bounds__(256) void score_grad_reduce_kernel(
     }
 }
 
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((u >> 16) | 0x40u);   // quiet NaN
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return static_cast<uint16_t>(u >> 16);
-}
-
 __global__ __launch_bounds__(256) void adamw_kernel(
     float* __restrict__ param, const float* __restrict__ grad, float* __restrict__ m, float* __restrict__ v,
     int64_t n, float lr, float beta1, float beta2, float eps, float weight_decay, float inv_bc1, float inv_bc2,

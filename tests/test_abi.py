@@ -30,7 +30,8 @@ def test_header_declares_the_five_stage_calls():
                "arrol_compact_workspace_bytes", "arrol_logprob_workspace_bytes", "arrol_version",
                "arrol_error_string", "arrol_set_tuning", "arrol_histogram", "arrol_calibrate",
                "arrol_prune_bernoulli", "arrol_compact_inplace", "arrol_compact_inplace_workspace_bytes",
-               "arrol_score_mlp", "arrol_score_grad", "arrol_score_grad_workspace_bytes", "arrol_adamw_step", "arrol_token_confidence",
+               "arrol_score_mlp", "arrol_score_grad", "arrol_score_grad_workspace_bytes", "arrol_adamw_step", "arrol_score_mlp_grad",
+               "arrol_score_mlp_grad_workspace_bytes", "arrol_token_confidence",
                "arrol_token_confidence_workspace_bytes", "arrol_trace_confidence",
                "arrol_trace_confidence_workspace_bytes", "arrol_grpo_advantage", "arrol_grpo_objective",
                "arrol_grpo_objective_workspace_bytes"]:
@@ -117,6 +118,16 @@ def test_bad_arguments_are_rejected_on_the_host(pkg):
     assert L.arrol_adamw_step(fake, fake, fake, fake, 8, 1, 1e-3, 1.0, 0.999, 1e-8, 0.0, None, None) == -1
     assert L.arrol_adamw_step(fake, None, fake, fake, 8, 1, 1e-3, 0.9, 0.999, 1e-8, 0.0, None, None) == -1
     assert L.arrol_adamw_step(None, None, None, None, 0, 1, 1e-3, 0.9, 0.999, 1e-8, 0.0, None, None) == 0
+    # MLP head gradient: bad d, m < 1, missing outputs, workspace missing / short / misaligned
+    mg = lambda d, m, gw1, ws, nbytes: L.arrol_score_mlp_grad(fake, 16, None, fake, None, fake, 0.0, fake, 4, d, m, None,
+                                                               gw1, fake, fake, None, ws, nbytes, None)
+    assert mg(12, 8, fake, fake, 1 << 24) == -1
+    assert mg(16, 0, fake, fake, 1 << 24) == -1
+    assert mg(16, 8, None, fake, 1 << 24) == -1
+    assert mg(16, 8, fake, None, 0) == -2
+    assert mg(16, 8, fake, fake, 256) == -2
+    assert mg(16, 8, fake, ctypes.c_void_p(0x1010), 1 << 24) == -2
+    assert L.arrol_score_mlp_grad_workspace_bytes(4, 16, 8) >= 3 * 4 * 4 + 128 * (16 + 8) * 2
     # trace confidence: bad d / V, null lse, workspace; aggregates: window < 1, percent outside [1, 100]
     assert L.arrol_token_confidence(fake, fake, fake, 4, 100, 12, fake, fake, 1 << 20, None) == -1
     assert L.arrol_token_confidence(fake, fake, fake, 4, 0, 16, fake, fake, 1 << 20, None) == -1

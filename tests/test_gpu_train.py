@@ -140,3 +140,103 @@ def test_head_training_loop_reduces_the_loss(A, W):
         w_o, m_o, v_o = O.adamw_step(w_o.astype(np.float32), gwo.astype(np.float32), m_o, v_o, t, float(np.float32(5e-2)))
         assert abs(losses[-1] - lo) <= 1e-4 * lo
     assert losses[-1] < losses[0]
+
+
+# ----------------------------------------------------------------------------- MLP head
+def mlp_case(n, d, m, seed):
+    g = torch.Generator(device=DEV); g.manual_seed(seed)
+    hidden = torch.randn(n, d, generator=g, device=DEV).to(torch.bfloat16)
+    w1 = (torch.randn(m, d, generator=g, device=DEV) * d ** -0.5).to(torch.bfloat16)
+    b1 = torch.randn(m, generator=g, device=DEV) * 0.1
+    w2 = torch.randn(m, generator=g, device=DEV) * m ** -0.5
+    labels = (torch.rand(n, generator=g, device=DEV) < 0.4).to(torch.float32)
+    return hidden, w1, b1, w2, labels
+
+
+def check_mlp_grad(A, hidden, w1, b1, w2, b2, labels, row_index=None):
+    out = A.arrol_score_mlp_grad(hidden, w1, b1, w2, b2, labels, row_index=row_index)
+    torch.cuda.synchronize()
+    hb = bits(hidden)
+    if row_index is not None:
+        hb = hb[npy(row_index)]
+    m = w1.shape[0]
+    b1n = np.zeros(m, np.float32) if b1 is None else npy(b1)
+    loss_o, gW1_o, gb1_o, gw2_o, gb2_o = O.score_mlp_ce_grad(hb, bits(w1), b1n, npy(w2), np.float32(b2), npy(labels))
+    n = hb.shape[0]
+    # quantities the tolerances are built from (float64, from the same inputs)
+    H = O.bf16_bits_to_f64(hb)
+    pre = H @ O.bf16_bits_to_f64(bits(w1)).T + b1n.astype(np.float64)             # [n, m]
+    s, q = O.score_mlp(hb, bits(w1), b1n, npy(w2), np.float32(b2))
+    r = (q - npy(labels).astype(np.float64)) / n
+    w2n = npy(w2).astype(np.float64)
+    delta = np.abs(r[:, None] * w2n[None, :]) * (pre > 0)                          # |delta| [n, m]
+    # a pre-activation within fp32 rounding of zero may gate differently in fp32 than in float64
+    near = np.abs(pre) < 4e-6 * (np.abs(H) @ np.abs(O.bf16_bits_to_f64(bits(w1))).T + 1.0)
+    flip = np.abs(r[:, None] * w2n[None, :]) * near
+    F32 = 4e-6
+    assert abs(float(out["loss"]) - loss_o) <= 1e-5 * max(1.0, abs(loss_o))
+    assert abs(float(out["grad_b2"]) - gb2_o) <= F32 * np.sum(np.abs(r)) + 1e-9
+    tol_b1 = F32 * delta.sum(axis=0) + flip.sum(axis=0) + 1e-9 * np.abs(w2n)
+    assert np.all(np.abs(npy(out["grad_b1"]) - gb1_o) <= tol_b1)
+    act = np.maximum(pre, 0.0)
+    tol_w2 = F32 * (np.abs(r)[:, None] * act).sum(axis=0) + 1e-9 * act.mean(axis=0) + 1e-12
+    assert np.all(np.abs(npy(out["grad_w2"]) - gw2_o) <= tol_w2)
+    # dL/dW1: delta is rounded to bf16 (unit roundoff 2^-8, worst case summed), fp32 accumulation on top
+    bound = (2.0 ** -8 + F32) * (delta.T @ np.abs(H)) + flip.T @ np.abs(H) + 1e-12
+    err = np.abs(npy(out["grad_w1"]).astype(np.float64) - gW1_o)
+    assert np.all(err <= bound), float((err / bound).max())
+    # rounding errors average out: the error as a whole is far below the worst case
+    if not near.any() and np.linalg.norm(gW1_o) > 0:
+        assert np.linalg.norm(err) <= 2.0 ** -8 * np.linalg.norm(gW1_o)
+    return out
+
+
+@pytest.mark.parametrize("n,d,m", [(1, 8, 1), (32, 256, 64), (130, 264, 100), (300, 1024, 257), (512, 2048, 512),
+                                   (1500, 512, 300)])
+def test_score_mlp_grad_matches_oracle(A, n, d, m):
+    print("[case] score_mlp_grad n=%d d=%d m=%d" % (n, d, m), flush=True)
+    hidden, w1, b1, w2, labels = mlp_case(n, d, m, seed=n + d + m)
+    check_mlp_grad(A, hidden, w1, b1, w2 * 4.0, -0.125, labels)
+
+
+def test_score_mlp_grad_gathered_rows_no_bias_dead_units_and_empty_batch(A):
+    print("[case] score_mlp_grad gathered / dead / empty", flush=True)
+    hidden, w1, b1, w2, _ = mlp_case(200, 128, 96, seed=5)
+    wide = torch.zeros(200, 160, dtype=torch.bfloat16, device=DEV)
+    wide[:, :128] = hidden
+    view = wide[:, :128]
+    g = torch.Generator(device=DEV); g.manual_seed(6)
+    idx = torch.randint(0, 200, (77,), generator=g, device=DEV, dtype=torch.int64)
+    soft = torch.rand(77, generator=g, device=DEV)
+    check_mlp_grad(A, view, w1, None, w2, 0.0, soft, row_index=idx)
+    dead = b1.clone()
+    dead[::3] = -1e4                                   # a third of the units never fire
+    out = check_mlp_grad(A, view, w1, dead, w2, 0.5, soft, row_index=idx)
+    assert torch.all(out["grad_w1"][::3] == 0) and torch.all(out["grad_b1"][::3] == 0) and torch.all(out["grad_w2"][::3] == 0)
+    out = A.arrol_score_mlp_grad(hidden[:0], w1, b1, w2, 0.0, soft[:0])
+    torch.cuda.synchronize()
+    assert float(out["loss"]) == 0.0 and float(out["grad_b2"]) == 0.0
+    assert not out["grad_w1"].any() and not out["grad_b1"].any() and not out["grad_w2"].any()
+
+
+def test_score_mlp_grad_is_reproducible_and_trains(A):
+    """Two calls give identical bits; gradient + AdamW on all four parameter sets lowers the loss."""
+    print("[case] score_mlp_grad reproducible / training loop", flush=True)
+    hidden, w1, b1, w2, labels = mlp_case(2048, 256, 128, seed=9)          # three K splits
+    o1 = A.arrol_score_mlp_grad(hidden, w1, b1, w2, 0.0, labels)
+    o2 = A.arrol_score_mlp_grad(hidden, w1, b1, w2, 0.0, labels)
+    torch.cuda.synchronize()
+    for k in o1:
+        assert torch.equal(o1[k], o2[k]), k
+    master = w1.float().clone()
+    params = [master.view(-1), b1.clone(), w2.clone()]
+    state = [(torch.zeros_like(p), torch.zeros_like(p)) for p in params]
+    w1_bf16 = w1.clone()
+    losses = []
+    for t in range(1, 9):
+        out = A.arrol_score_mlp_grad(hidden, w1_bf16, params[1], params[2], 0.0, labels)
+        losses.append(float(out["loss"]))
+        grads = [out["grad_w1"].view(-1), out["grad_b1"], out["grad_w2"]]
+        for k, (p, gk, (mk, vk)) in enumerate(zip(params, grads, state)):
+            A.arrol_adamw_step(p, gk, mk, vk, t, lr=1e-2, param_bf16=w1_bf16.view(-1) if k == 0 else None)
+    assert losses[-1] < losses[0] - 0.01, losses
