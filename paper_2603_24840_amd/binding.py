@@ -423,12 +423,14 @@ def arrol_grpo_objective(logp, logp_ref, cu_seqlens, advantage, seq_weight, eps_
     return J, grad, n_clip
 
 
-def arrol_weighted_vote(prob, answer_id, n_questions, C, n_answers, want_tally=False, stream=None):
+def arrol_weighted_vote(prob, answer_id, n_questions, C, n_answers, want_tally=False, out_winner=None, stream=None):
     """prob fp32 [Q*C], answer_id int32 [Q*C] -> winner int32 [Q] (and tally int64 [Q, A])."""
     dev = prob.device
     if prob.numel() != n_questions * C or answer_id.numel() != n_questions * C:
         raise ValueError("prob and answer_id must have n_questions*C entries")
-    winner = torch.empty(n_questions, dtype=torch.int32, device=dev)
+    winner = out_winner if out_winner is not None else torch.empty(n_questions, dtype=torch.int32, device=dev)
+    if winner.numel() != n_questions:
+        raise ValueError("out_winner must have n_questions entries")
     tally = torch.empty((n_questions, n_answers), dtype=torch.int64, device=dev) if want_tally else None
     rc = lib().arrol_weighted_vote(_ptr(prob, torch.float32, "prob"), _ptr(answer_id, torch.int32, "answer_id"),
                                    n_questions, C, n_answers, _ptr(winner, torch.int32, "winner"),
