@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
 #include "arrol.h"
 
 #define ARROL_WAVE 64
@@ -13,15 +14,17 @@ static inline int arrol_launch_status() {
     return hipGetLastError() == hipSuccess ? ARROL_OK : ARROL_EHIP;
 }
 
-// Raises a kernel's dynamic-LDS limit once per device (function attributes are per device).
+// Raises a kernel's dynamic-LDS limit once per device (function attributes are per device); `bytes` is the
+// most the kernel is ever launched with.  Safe to call from several host threads.
+typedef std::atomic<bool> arrol_device_flags[64];
 template <class K>
-static inline bool arrol_allow_lds(K kernel, int bytes, bool (&done)[64]) {
+static inline bool arrol_allow_lds(K kernel, int bytes, arrol_device_flags& done) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false;
-    if (done[dev]) return true;
+    if (done[dev].load(std::memory_order_acquire)) return true;
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess)
         return false;
-    done[dev] = true;
+    done[dev].store(true, std::memory_order_release);
     return true;
 }
 

@@ -42,25 +42,6 @@ __global__ __launch_bounds__(kColThreads) void colsum_partial_kernel(
     }
 }
 
-// colsum[c] = sum over blocks, in a fixed order: 32 columns x 8 block-groups per workgroup
-__global__ __launch_bounds__(256) void colsum_reduce_kernel(const float* __restrict__ partial, int n_partials,
-                                                            int d, float* __restrict__ colsum) {
-    __shared__ float red[8][32];
-    const int cx = threadIdx.x & 31, ry = threadIdx.x >> 5;
-    const int col = blockIdx.x * 32 + cx;
-    float s = 0.f;
-    if (col < d)
-        for (int p = ry; p < n_partials; p += 8) s += partial[static_cast<int64_t>(p) * d + col];
-    red[ry][cx] = s;
-    __syncthreads();
-    if (ry == 0 && col < d) {
-        float t = 0.f;
-#pragma unroll
-        for (int k = 0; k < 8; ++k) t += red[k][cx];
-        colsum[col] = t;
-    }
-}
-
 constexpr int kConfThreads = 512;
 constexpr int kConfWaves = kConfThreads / ARROL_WAVE;
 constexpr int kConfUnroll = 4;
@@ -274,9 +255,10 @@ extern "C" int arrol_token_confidence(const void* hidden, const void* lm_head, c
     float* partial = colsum + d;
     hipLaunchKernelGGL(colsum_partial_kernel, dim3(nb), dim3(kColThreads), 0, st,
                        static_cast<const u32x4*>(lm_head), V, d / 8, partial);
-    hipLaunchKernelGGL(colsum_reduce_kernel, dim3((d + 31) / 32), dim3(256), 0, st, partial, nb, d, colsum);
-    static bool lds_ok[64] = {};
-    if (!arrol_allow_lds(token_conf_kernel, static_cast<int>(sizeof(float) * d), lds_ok)) return ARROL_EHIP;
+    hipLaunchKernelGGL(reduce_rows_f32_kernel<0>, dim3((d + 31) / 32), dim3(256), 0, st, partial, nb,
+                       static_cast<int64_t>(d), static_cast<int64_t>(d), 1.f, colsum);
+    static arrol_device_flags lds_ok;
+    if (!arrol_allow_lds(token_conf_kernel, static_cast<int>(sizeof(float) * 16384), lds_ok)) return ARROL_EHIP;
     const int64_t blocks_needed = (T + kConfWaves - 1) / kConfWaves;
     const int grid = static_cast<int>(blocks_needed < 256 * 8 ? blocks_needed : 256 * 8);
     hipLaunchKernelGGL(token_conf_kernel, dim3(grid), dim3(kConfThreads), sizeof(float) * d, st,

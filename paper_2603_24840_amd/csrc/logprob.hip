@@ -624,7 +624,7 @@ extern "C" int arrol_logprob(const void* hidden, const void* lm_head, const int3
     if (!workspace || !arrol_aligned16(workspace) || workspace_bytes < arrol_logprob_workspace_bytes(T, V, d))
         return ARROL_EWORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    static bool general_ok[64] = {}, fast_ok[64] = {};
+    static arrol_device_flags general_ok, fast_ok;
     if (!arrol_allow_lds(&logprob_kernel<MainTile>, MainTile::LDS_BYTES, general_ok) ||
         !arrol_allow_lds(&logprob_ring_kernel<FastTile>, FastTile::LDS_BYTES, fast_ok))
         return ARROL_EHIP;

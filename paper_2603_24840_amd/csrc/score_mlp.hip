@@ -320,7 +320,7 @@ GradPlan make_grad_plan(int n_rows, int d, int m) {
 
 template <int MODE>
 int launch_mlp(const MlpArgs& a, dim3 grid, hipStream_t st) {
-    static bool lds_ok[64] = {};
+    static arrol_device_flags lds_ok;
     if (!arrol_allow_lds(&score_mlp_kernel<MODE>, kLdsBytes, lds_ok)) return ARROL_EHIP;
     hipLaunchKernelGGL(score_mlp_kernel<MODE>, grid, dim3(kThreads), kLdsBytes, st, a);
     return arrol_launch_status();

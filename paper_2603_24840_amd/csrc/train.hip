@@ -167,8 +167,9 @@ template <int CH>
 int launch_grad(int grid, size_t lds_bytes, hipStream_t st, const void* hidden, int64_t row_stride_vec,
                 const int64_t* row_index, const float* w, float bias, const float* labels, int n_rows, int d_vec,
                 float* partial, float* tail) {
-    static bool lds_ok[64] = {};
-    if (!arrol_allow_lds(score_grad_kernel<CH>, static_cast<int>(lds_bytes), lds_ok)) return ARROL_EHIP;
+    static arrol_device_flags lds_ok;
+    if (!arrol_allow_lds(score_grad_kernel<CH>, static_cast<int>(sizeof(float) * (kGradMaxD + kGradWaves * 512)), lds_ok))
+        return ARROL_EHIP;
     hipLaunchKernelGGL(score_grad_kernel<CH>, dim3(grid), dim3(kGradThreads), lds_bytes, st,
                        static_cast<const u32x4*>(hidden), row_stride_vec, row_index, w, bias, labels, n_rows, d_vec,
                        partial, tail);
