@@ -37,7 +37,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="llama1b")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-rows", type=int, default=8192)
+    ap.add_argument("--cpu-sample-rows", type=int, default=24576)
     ap.add_argument("--calibrate-copy", action="store_true")
     ap.add_argument("--inplace-compaction", action="store_true",
                     help="also time arrol_compact_inplace on the same pool and survivors (extra JSON object)")
