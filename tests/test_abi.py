@@ -185,3 +185,15 @@ def test_binding_refuses_cpu_tensors(pkg):
         pkg.arrol_score(h, torch.zeros(16))
     with pytest.raises(ValueError):
         pkg.arrol_select(torch.zeros(8), 1, 8, 4)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU: `bench.py --gpus N` with N > 1 exits with a message that says so."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                         timeout=120)
+    assert res.returncode == 2
+    assert "ONE GPU" in res.stderr and "--gpus 2" in res.stderr
+    assert res.stdout.strip() == ""
