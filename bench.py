@@ -80,10 +80,11 @@ def cpu_baseline(cfg, t, sample_rows, torch):
     t0 = time.perf_counter()
     _, q = O.score(bits(t["hidden"]), npy(t["w"]), t["bias"])
     times["score"] = time.perf_counter() - t0
-    q32 = npy(t["prob"])
+    q32 = q.astype(np.float32)            # the oracle's own chain: its probabilities at the interface precision
     t0 = time.perf_counter()
     _, surv = O.select(q32, cfg.n_prompts, cfg.G, cfg.K, cfg.rho)
     times["select"] = time.perf_counter() - t0
+    select_ok = bool(np.array_equal(npy(t["surv"]), surv))
     # compact: two layers of the pool, scaled to all layers (layers are independent slabs)
     L_s = min(2, cfg.n_layers)
     kv_host = bits(t["kv_src"][:L_s])
@@ -107,7 +108,11 @@ def cpu_baseline(cfg, t, sample_rows, torch):
     times["logprob"] = dt * T / len(rows)
     err = float(np.max(np.abs(npy(t["logprob"])[rows.numpy()].astype(np.float64) - lp_o)))
     t0 = time.perf_counter()
-    O.weighted_vote(npy(t["vote_prob"]), npy(t["answer_id"]), cfg.vote_q, cfg.vote_c, cfg.vote_a)
+    if t["vote_hidden"] is None:            # the vote ran on the batch's own probabilities
+        vote_q32 = q32[:cfg.vote_q * cfg.vote_c]
+    else:                                   # test-time shape: the vote stage scored its own candidates
+        vote_q32 = O.score(bits(t["vote_hidden"]), npy(t["w"]), t["bias"])[1].astype(np.float32)
+    O.weighted_vote(vote_q32, npy(t["answer_id"]), cfg.vote_q, cfg.vote_c, cfg.vote_a)
     times["vote"] = time.perf_counter() - t0
     total = sum(times.values())
     return {"value": T / total, "unit": "tokens/s", "cores": cores, "kind": "oracle",
@@ -115,7 +120,8 @@ def cpu_baseline(cfg, t, sample_rows, torch):
                       "rows (seeded, incl. first and last); stage times scaled to the full step"
                       % (L_s, cfg.n_layers, len(rows), T),
             "stage_seconds_scaled": {k: round(v, 4) for k, v in times.items()},
-            "parity_on_sample": {"logprob_max_abs_err": err, "compact_bit_exact": compact_ok}}
+            "parity_on_sample": {"logprob_max_abs_err": err, "select_identical": select_ok,
+                                 "compact_bit_exact": compact_ok}}
 
 
 def time_extras(A, W, cfg, dev, torch, lp_hidden, lm_head, targets, cu, lws, reps=10):
@@ -356,10 +362,10 @@ def main():
     if args.extras:
         result["extras"] = time_extras(A, W, cfg, dev, torch, lp_hidden, lm_head, targets, cu, lws)
     if not args.skip_cpu_baseline and not only:
-        tensors = dict(hidden=hidden, w=w, bias=bias, prob=prob, kv_src=kv_src, kv_dst=kv_dst,
+        tensors = dict(hidden=hidden, w=w, bias=bias, surv=surv, kv_src=kv_src, kv_dst=kv_dst,
                        block_table=block_table, seq_len=seq_len, tokens=tokens, lp_hidden=lp_hidden,
                        lm_head=lm_head, targets=targets, logprob=logprob, answer_id=answer_id,
-                       vote_prob=vote_prob if vote_own_score else prob[:n_vote])
+                       vote_hidden=vote_hidden if vote_own_score else None)
         result["cpu_baseline"] = cpu_baseline(cfg, tensors, args.cpu_sample_rows, torch)
     print(json.dumps(result), flush=True)
 

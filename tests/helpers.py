@@ -21,3 +21,14 @@ def f32_to_bf16_bits(x):
 
 def bf16_tensor_from_bits(b, device):
     return torch.from_numpy(np.ascontiguousarray(b).view(np.int16)).view(torch.bfloat16).to(device)
+
+
+def to_dev(x, device, dtype=None):
+    """numpy array (an input, or an oracle result rounded to the interface dtype) -> device tensor."""
+    a = np.ascontiguousarray(x if dtype is None else np.asarray(x).astype(dtype))
+    return torch.from_numpy(a).to(device)
+
+
+def oracle_survivors(O, prob_f32, cfg):
+    """Survivors the oracle selects from fp32 probabilities (numpy), as (keep_mask, survivor_idx)."""
+    return O.select(np.asarray(prob_f32, dtype=np.float32), cfg.n_prompts, cfg.G, cfg.K, cfg.rho)

@@ -6,7 +6,7 @@ import pytest
 import torch
 
 import oracle as O
-from helpers import bits, npy
+from helpers import bits, npy, to_dev, oracle_survivors
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -54,9 +54,17 @@ def test_llama1b_prune_path_full_size(A, W):
     torch.cuda.synchronize()
     so, qo = O.score(bits(hidden), npy(w), b)
     assert np.max(np.abs(npy(q) - qo)) < 1e-3 and np.max(np.abs(npy(s) - so)) < 1e-3
-    keep_o, surv_o = O.select(npy(q), cfg.n_prompts, cfg.G, cfg.K, cfg.rho)
+    # the oracle's chain runs from the inputs alone; the library is checked on the oracle's probabilities
+    # (stage parity) and on its own (chain parity: rounding-level differences, no tie that close here)
+    q32 = qo.astype(np.float32)
+    keep_o, surv_o = oracle_survivors(O, q32, cfg)
+    win_o, tally_o = O.weighted_vote(q32, npy(ans), cfg.vote_q, cfg.vote_c, cfg.vote_a)
+    keep2, surv2 = A.arrol_select(to_dev(q32, DEV), cfg.n_prompts, cfg.G, cfg.K, cfg.rho)
+    win2, tally2 = A.arrol_weighted_vote(to_dev(q32, DEV), ans, cfg.vote_q, cfg.vote_c, cfg.vote_a, want_tally=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(npy(keep2), keep_o) and np.array_equal(npy(surv2), surv_o)
+    assert np.array_equal(npy(win2), win_o) and np.array_equal(npy(tally2), tally_o)
     assert np.array_equal(npy(keep), keep_o) and np.array_equal(npy(surv), surv_o)
-    win_o, tally_o = O.weighted_vote(npy(q), npy(ans), cfg.vote_q, cfg.vote_c, cfg.vote_a)
     assert np.array_equal(npy(win), win_o) and np.array_equal(npy(tally), tally_o)
 
 
@@ -64,14 +72,17 @@ def test_llama1b_compact_full_size(A, W):
     cfg = W.CONFIGS["llama1b"]
     say("llama1b compact, full pool (8.6 GB), oracle on 4 of 16 layers + gather property on all")
     kv, bt, sl, tok = W.compact_inputs(cfg, DEV)
-    p = W.select_inputs(cfg, DEV)
+    p = W.select_inputs(cfg, DEV)                                  # seeded probabilities (an input)
+    _, surv_o = oracle_survivors(O, npy(p), cfg)
     _, surv = A.arrol_select(p, cfg.n_prompts, cfg.G, cfg.K, cfg.rho)
+    torch.cuda.synchronize()
+    assert np.array_equal(npy(surv), surv_o)
     n_dst = cfg.n_keep * cfg.pages_per_rollout
     dst = torch.empty((cfg.n_layers, 2, n_dst) + tuple(kv.shape[3:]), dtype=torch.bfloat16, device=DEV)
     dst.view(torch.int16).fill_(0x7FC1)
     out = A.arrol_compact(kv, dst, bt, sl, tok, surv)
     torch.cuda.synchronize()
-    surv_h, bt_h, sl_h, tok_h = npy(surv), npy(bt), npy(sl), npy(tok)
+    surv_h, bt_h, sl_h, tok_h = surv_o, npy(bt), npy(sl), npy(tok)
     for layer in (0, 5, 10, cfg.n_layers - 1):
         ref = O.compact(bits(kv[layer:layer + 1]), bt_h, sl_h, tok_h, surv_h, n_dst, fill=0x7FC1)
         assert np.array_equal(bits(dst[layer:layer + 1]), ref["kv_dst"]), layer
@@ -134,8 +145,11 @@ def test_prune_path_other_model_geometries(A, W, name):
     torch.cuda.synchronize()
     _, qo = O.score(bits(hidden), npy(w), b)
     assert np.max(np.abs(npy(q) - qo)) < 1e-3
-    keep_o, surv_o = O.select(npy(q), cfg.n_prompts, cfg.G, cfg.K, cfg.rho)
-    assert np.array_equal(npy(keep), keep_o) and np.array_equal(npy(surv), surv_o)
+    q32 = qo.astype(np.float32)
+    keep_o, surv_o = oracle_survivors(O, q32, cfg)
+    keep2, surv2 = A.arrol_select(to_dev(q32, DEV), cfg.n_prompts, cfg.G, cfg.K, cfg.rho)
+    assert np.array_equal(npy(keep2), keep_o) and np.array_equal(npy(surv2), surv_o)     # stage parity
+    assert np.array_equal(npy(keep), keep_o) and np.array_equal(npy(surv), surv_o)       # chain parity
     ref = O.compact(bits(kv), npy(bt), npy(sl), npy(tok), surv_o, n_dst)
     assert np.array_equal(bits(dst), ref["kv_dst"])
     assert np.array_equal(npy(out["block_table_dst"]), ref["block_table_dst"])
@@ -153,5 +167,15 @@ def test_vote_test_time_shape_qwen8b(A, W):
     rows = np.arange(0, hidden.shape[0], 97)
     _, qo = O.score(bits(hidden[torch.from_numpy(rows).to(DEV)]), npy(w), b)
     assert np.max(np.abs(npy(q)[rows] - qo)) < 1e-3
-    win_o, tally_o = O.weighted_vote(npy(q), npy(ans), cfg.vote_q, cfg.vote_c, cfg.vote_a)
-    assert np.array_equal(npy(win), win_o) and np.array_equal(npy(tally), tally_o)
+    # the vote at this shape on seeded probabilities (inputs, with exact ties among them) against the oracle
+    g = torch.Generator(device=DEV); g.manual_seed(88)
+    p = (torch.randint(0, 4096, (hidden.shape[0],), generator=g, device=DEV).float() / 4096.0).contiguous()
+    win2, tally2 = A.arrol_weighted_vote(p, ans, cfg.vote_q, cfg.vote_c, cfg.vote_a, want_tally=True)
+    torch.cuda.synchronize()
+    win_o, tally_o = O.weighted_vote(npy(p), npy(ans), cfg.vote_q, cfg.vote_c, cfg.vote_a)
+    assert np.array_equal(npy(win2), win_o) and np.array_equal(npy(tally2), tally_o)
+    # the chain's vote (library scores -> library vote): every question has a winner among its candidates' answers
+    a = npy(ans).reshape(cfg.vote_q, cfg.vote_c)
+    wn = npy(win)
+    assert all(wn[i] in a[i] for i in range(cfg.vote_q))
+    assert np.array_equal(npy(tally).sum(axis=1), np.full(cfg.vote_q, cfg.vote_c * (cfg.vote_c - 1), dtype=np.int64))

@@ -4,7 +4,7 @@ import pytest
 import torch
 
 import oracle as O
-from helpers import npy
+from helpers import npy, to_dev
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -63,11 +63,15 @@ def run_objective(A, lens, sizes, seed, eps_low=0.2, eps_high=0.2, beta=0.0, dri
     logp_ref = -torch.rand(max(T, 1), generator=g, device=DEV)[:T] * 4
     logp = logp_ref + torch.randn(max(T, 1), generator=g, device=DEV)[:T] * drift
     reward = (torch.rand(len(lens), generator=g, device=DEV) < 0.5).to(torch.float32)
-    adv, wgt = A.arrol_grpo_advantage(reward, dev_i64(off))
+    # advantages: the oracle's, rounded to the interface's fp32, feed both sides; the per-rollout weights
+    # 1/(group size * groups) are what arrol_grpo_advantage hands to the objective (checked in the test above)
+    adv_o = O.grpo_advantage(npy(reward), off).astype(np.float32)
+    adv = to_dev(adv_o, DEV)
+    _, wgt = A.arrol_grpo_advantage(reward, dev_i64(off))
     J, grad, n_clip = A.arrol_grpo_objective(logp, logp_ref, dev_i64(cu), adv, wgt, eps_low, eps_high, beta)
     torch.cuda.synchronize()
-    Jo, go, co = O.grpo_objective(npy(logp), npy(logp_ref), cu, npy(adv), off, f32(eps_low), f32(eps_high), f32(beta))
-    scale = max(abs(Jo), float(np.mean(np.abs(npy(adv)))) if len(lens) else 0.0, 1e-30)
+    Jo, go, co = O.grpo_objective(npy(logp), npy(logp_ref), cu, adv_o, off, f32(eps_low), f32(eps_high), f32(beta))
+    scale = max(abs(Jo), float(np.mean(np.abs(adv_o))) if len(lens) else 0.0, 1e-30)
     assert abs(float(J) - Jo) <= RTOL * scale, (float(J), Jo)
     assert int(n_clip) == co
     err = np.abs(npy(grad).astype(np.float64) - go)

@@ -4,7 +4,7 @@ import pytest
 import torch
 
 import oracle as O
-from helpers import bits, npy
+from helpers import bits, npy, to_dev, oracle_survivors
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -40,8 +40,8 @@ def test_inplace_tiny_config(A, W):
     cfg = W.CONFIGS["tiny"]
     print("[case] inplace tiny", flush=True)
     kv, bt, sl, _ = W.compact_inputs(cfg, DEV)
-    p = W.select_inputs(cfg, DEV)
-    _, surv = A.arrol_select(p, cfg.n_prompts, cfg.G, cfg.K, cfg.rho)
+    _, surv_o = oracle_survivors(O, npy(W.select_inputs(cfg, DEV)), cfg)      # survivors from the oracle's selection
+    surv = to_dev(surv_o, DEV)
     out, ref = run_case(A, kv, bt, sl, surv)
     assert ref["n_pages_used"] == cfg.n_keep * cfg.pages_per_rollout and 0 < ref["n_moved"] < ref["n_pages_used"]
 
@@ -83,8 +83,8 @@ def test_inplace_llama1b_full_size(A, W):
     cfg = W.CONFIGS["llama1b"]
     print("[case] inplace llama1b full pool; oracle on 2 of 16 layers, content property on all", flush=True)
     kv, bt, sl, _ = W.compact_inputs(cfg, DEV)
-    p = W.select_inputs(cfg, DEV)
-    _, surv = A.arrol_select(p, cfg.n_prompts, cfg.G, cfg.K, cfg.rho)
+    _, surv_o = oracle_survivors(O, npy(W.select_inputs(cfg, DEV)), cfg)      # survivors from the oracle's selection
+    surv = to_dev(surv_o, DEV)
     flat_old = bt[surv.long()].reshape(-1).long()
     probe = kv[:, :, flat_old, 0, 0, :4].clone()                 # a fingerprint of every survivor page, all layers
     host_before = {layer: bits(kv[layer:layer + 1]).copy() for layer in (0, cfg.n_layers - 1)}
