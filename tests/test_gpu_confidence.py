@@ -4,7 +4,7 @@ import pytest
 import torch
 
 import oracle as O
-from helpers import bits, npy
+from helpers import bits, npy, to_dev
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -37,9 +37,16 @@ def test_token_confidence_matches_oracle(A, W, T, V, d):
     cfg = W.shrink(W.CONFIGS["tiny"], d=d, vocab=V)
     hidden, lm_head, targets, _ = W.logprob_inputs(cfg, DEV, T=T, vocab=V)
     _, lse = A.arrol_logprob(hidden, lm_head, targets, want_lse=True)
-    conf = A.arrol_token_confidence(hidden, lm_head, lse)
-    torch.cuda.synchronize()
+    conf = A.arrol_token_confidence(hidden, lm_head, lse)                     # the library's chain
     ref = O.token_confidence(bits(hidden), bits(lm_head))
+    _, lse_o = O.logprob(bits(hidden), bits(lm_head), npy(targets))
+    lse32 = lse_o.astype(np.float32)
+    conf2 = A.arrol_token_confidence(hidden, lm_head, to_dev(lse32, DEV))     # the stage on the oracle's lse
+    torch.cuda.synchronize()
+    # stage parity: only the fp32 rounding of lse (times V), the fp32 dot product and the fp32 result remain
+    tol2 = V * np.abs(lse32 - lse_o) + 1e-5 * np.sqrt(V) + 2e-6 * np.abs(ref)
+    err2 = np.abs(npy(conf2).astype(np.float64) - ref)
+    assert np.all(err2 <= tol2), (float((err2 / tol2).max()), float(err2.max()))
     err = np.abs(npy(conf).astype(np.float64) - ref)
     assert np.all(err <= conf_tol(V, ref)), (float(err.max()), float(np.abs(ref).max()))
 
@@ -51,13 +58,12 @@ def test_token_confidence_peaked_distribution(A):
     hidden = (torch.randn(24, 64, generator=g, device=DEV) * 4).to(torch.bfloat16)
     lm_head = (torch.randn(900, 64, generator=g, device=DEV)).to(torch.bfloat16)
     targets = torch.zeros(24, dtype=torch.int32, device=DEV)
-    _, lse = A.arrol_logprob(hidden, lm_head, targets, want_lse=True)
-    conf = A.arrol_token_confidence(hidden, lm_head, lse)
-    torch.cuda.synchronize()
     ref = O.token_confidence(bits(hidden), bits(lm_head))
     _, lse_o = O.logprob(bits(hidden), bits(lm_head), npy(targets))
-    # tolerance from the lse actually fed in: V * |lse_gpu - lse_oracle| plus fp32 rounding of the result
-    tol = 900 * np.abs(npy(lse).astype(np.float64) - lse_o) + 2e-6 * np.abs(ref) + 1e-3
+    lse32 = lse_o.astype(np.float32)
+    conf = A.arrol_token_confidence(hidden, lm_head, to_dev(lse32, DEV))      # the stage on the oracle's lse
+    torch.cuda.synchronize()
+    tol = 900 * np.abs(lse32 - lse_o) + 2e-6 * np.abs(ref) + 1e-3
     assert np.all(np.abs(npy(conf).astype(np.float64) - ref) <= tol)
 
 
