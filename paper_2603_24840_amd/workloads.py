@@ -2,7 +2,10 @@
 
 Input generation only: nothing of the method's arithmetic lives here.  Both the HIP
 path and the CPU oracle are fed from these generators (tensors are produced once, on the
-requested device, and copied to the host for the oracle).
+requested device, and copied to the host for the oracle).  Where a generator squashes random
+scores with torch.sigmoid it only shapes the distribution of a synthetic INPUT (probabilities
+fed to the selection, labelled score buffers, reward labels); neither the library's nor the
+oracle's scoring is involved.
 """
 from dataclasses import dataclass, replace
 
