@@ -334,6 +334,11 @@ def main():
                              "frac": (kv_bytes + meta_bytes) / cp_s / 1e9 / HBM_PEAK_GBPS if cp_s > 0 else 0.0,
                              "traffic": PROFILED_TRAFFIC_BYTES.get((cfg.name, "compact"))},
         "prune_compact_GBps": (prune_bytes + kv_bytes + meta_bytes) / pc_s / 1e9 if pc_s > 0 else 0.0,
+        # algorithmic bytes of each HBM-bound stage over its own event time (score and select are
+        # launch-latency bound at training shapes: a few microseconds for a few megabytes)
+        "stage_GBps": {"score": (N * cfg.d * 2 + cfg.d * 4 + N * 8) / stage_ms["score"] / 1e6 if stage_ms["score"] > 0 else 0.0,
+                       "select": (N * 4 + N + 4 * Nk) / stage_ms["select"] / 1e6 if stage_ms["select"] > 0 else 0.0,
+                       "compact": (kv_bytes + meta_bytes) / stage_ms["compact"] / 1e6 if stage_ms["compact"] > 0 else 0.0},
         "logprob_tokens_per_s": T / lp_s if lp_s > 0 else 0.0,
         "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
     }
