@@ -46,40 +46,69 @@ constexpr int kConfThreads = 512;
 constexpr int kConfWaves = kConfThreads / ARROL_WAVE;
 constexpr int kConfUnroll = 4;
 
-// one wavefront per token: conf[t] = V * lse[t] - <h_t, colsum>
+// one wavefront per token: conf[t] = V * lse[t] - <h_t, colsum>.  CH > 0: lane l owns chunks c*64 + l (c < CH) of
+// every row and keeps its slice of colsum in registers (d <= 512*CH); CH == 0: colsum staged in LDS, any d.
+template <int CH>
 __global__ __launch_bounds__(kConfThreads) void token_conf_kernel(
     const u32x4* __restrict__ hidden, const float* __restrict__ colsum, const float* __restrict__ lse,
     int64_t T, int V, int d_vec, float* __restrict__ conf) {
     extern __shared__ float c_lds[];
-    for (int i = threadIdx.x; i < d_vec * 8; i += kConfThreads) c_lds[i] = colsum[i];
-    __syncthreads();
     const int lane = threadIdx.x & (ARROL_WAVE - 1);
     const int wave = threadIdx.x / ARROL_WAVE;
+    constexpr int NR = CH > 0 ? CH : 1;
+    float4 wa[NR], wb[NR];
+    if (CH > 0) {
+#pragma unroll
+        for (int c = 0; c < NR; ++c) {
+            const int v = c * ARROL_WAVE + lane;
+            wa[c] = v < d_vec ? *reinterpret_cast<const float4*>(colsum + v * 8) : make_float4(0.f, 0.f, 0.f, 0.f);
+            wb[c] = v < d_vec ? *reinterpret_cast<const float4*>(colsum + v * 8 + 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    } else {
+        for (int i = threadIdx.x; i < d_vec * 8; i += kConfThreads) c_lds[i] = colsum[i];
+        __syncthreads();
+    }
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kConfWaves;
     for (int64_t t = static_cast<int64_t>(blockIdx.x) * kConfWaves + wave; t < T; t += stride) {
         const u32x4* p = hidden + t * d_vec;
-        float acc0 = 0.f, acc1 = 0.f;
-        for (int v0 = 0; v0 < d_vec; v0 += kConfUnroll * ARROL_WAVE) {
-            u32x4 x[kConfUnroll];
+        float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
+        if (CH > 0) {
+            u32x4 x[NR];
 #pragma unroll
-            for (int u = 0; u < kConfUnroll; ++u) {
-                const int v = v0 + u * ARROL_WAVE + lane;
-                x[u] = v < d_vec ? __builtin_nontemporal_load(p + v) : u32x4{0u, 0u, 0u, 0u};
+            for (int c = 0; c < NR; ++c) {
+                const int v = c * ARROL_WAVE + lane;
+                x[c] = v < d_vec ? __builtin_nontemporal_load(p + v) : u32x4{0u, 0u, 0u, 0u};
             }
 #pragma unroll
-            for (int u = 0; u < kConfUnroll; ++u) {
-                const int v = v0 + u * ARROL_WAVE + lane;
-                if (v < d_vec) {
-                    const float4 wa = *reinterpret_cast<const float4*>(c_lds + v * 8);
-                    const float4 wb = *reinterpret_cast<const float4*>(c_lds + v * 8 + 4);
-                    acc0 = fmaf(bf16_lo(x[u].x), wa.x, acc0); acc1 = fmaf(bf16_hi(x[u].x), wa.y, acc1);
-                    acc0 = fmaf(bf16_lo(x[u].y), wa.z, acc0); acc1 = fmaf(bf16_hi(x[u].y), wa.w, acc1);
-                    acc0 = fmaf(bf16_lo(x[u].z), wb.x, acc0); acc1 = fmaf(bf16_hi(x[u].z), wb.y, acc1);
-                    acc0 = fmaf(bf16_lo(x[u].w), wb.z, acc0); acc1 = fmaf(bf16_hi(x[u].w), wb.w, acc1);
+            for (int c = 0; c < NR; ++c) {
+                acc0 = fmaf(bf16_lo(x[c].x), wa[c].x, acc0); acc1 = fmaf(bf16_hi(x[c].x), wa[c].y, acc1);
+                acc2 = fmaf(bf16_lo(x[c].y), wa[c].z, acc2); acc3 = fmaf(bf16_hi(x[c].y), wa[c].w, acc3);
+                acc0 = fmaf(bf16_lo(x[c].z), wb[c].x, acc0); acc1 = fmaf(bf16_hi(x[c].z), wb[c].y, acc1);
+                acc2 = fmaf(bf16_lo(x[c].w), wb[c].z, acc2); acc3 = fmaf(bf16_hi(x[c].w), wb[c].w, acc3);
+            }
+        } else {
+            for (int v0 = 0; v0 < d_vec; v0 += kConfUnroll * ARROL_WAVE) {
+                u32x4 x[kConfUnroll];
+#pragma unroll
+                for (int u = 0; u < kConfUnroll; ++u) {
+                    const int v = v0 + u * ARROL_WAVE + lane;
+                    x[u] = v < d_vec ? __builtin_nontemporal_load(p + v) : u32x4{0u, 0u, 0u, 0u};
+                }
+#pragma unroll
+                for (int u = 0; u < kConfUnroll; ++u) {
+                    const int v = v0 + u * ARROL_WAVE + lane;
+                    if (v < d_vec) {
+                        const float4 la = *reinterpret_cast<const float4*>(c_lds + v * 8);
+                        const float4 lb = *reinterpret_cast<const float4*>(c_lds + v * 8 + 4);
+                        acc0 = fmaf(bf16_lo(x[u].x), la.x, acc0); acc1 = fmaf(bf16_hi(x[u].x), la.y, acc1);
+                        acc2 = fmaf(bf16_lo(x[u].y), la.z, acc2); acc3 = fmaf(bf16_hi(x[u].y), la.w, acc3);
+                        acc0 = fmaf(bf16_lo(x[u].z), lb.x, acc0); acc1 = fmaf(bf16_hi(x[u].z), lb.y, acc1);
+                        acc2 = fmaf(bf16_lo(x[u].w), lb.z, acc2); acc3 = fmaf(bf16_hi(x[u].w), lb.w, acc3);
+                    }
                 }
             }
         }
-        const float dot = wave_sum_f32(acc0 + acc1);
+        const float dot = wave_sum_f32((acc0 + acc1) + (acc2 + acc3));
         if (lane == 0)
             conf[t] = static_cast<float>(static_cast<double>(V) * static_cast<double>(lse[t]) -
                                          static_cast<double>(dot));
@@ -257,12 +286,21 @@ extern "C" int arrol_token_confidence(const void* hidden, const void* lm_head, c
                        static_cast<const u32x4*>(lm_head), V, d / 8, partial);
     hipLaunchKernelGGL(reduce_rows_f32_kernel<0>, dim3((d + 31) / 32), dim3(256), 0, st, partial, nb,
                        static_cast<int64_t>(d), static_cast<int64_t>(d), 1.f, colsum);
-    static arrol_device_flags lds_ok;
-    if (!arrol_allow_lds(token_conf_kernel, static_cast<int>(sizeof(float) * 16384), lds_ok)) return ARROL_EHIP;
     const int64_t blocks_needed = (T + kConfWaves - 1) / kConfWaves;
     const int grid = static_cast<int>(blocks_needed < 256 * 8 ? blocks_needed : 256 * 8);
-    hipLaunchKernelGGL(token_conf_kernel, dim3(grid), dim3(kConfThreads), sizeof(float) * d, st,
-                       static_cast<const u32x4*>(hidden), colsum, lse, T, V, d / 8, conf_out);
+    const u32x4* h = static_cast<const u32x4*>(hidden);
+    const int chunks = (d / 8 + ARROL_WAVE - 1) / ARROL_WAVE;
+#define ARROL_CONF(CH, LDS) hipLaunchKernelGGL(token_conf_kernel<CH>, dim3(grid), dim3(kConfThreads), LDS, st, h, colsum, lse, T, V, d / 8, conf_out)
+    if (chunks <= 1) ARROL_CONF(1, 0);
+    else if (chunks <= 2) ARROL_CONF(2, 0);
+    else if (chunks <= 4) ARROL_CONF(4, 0);
+    else if (chunks <= 8) ARROL_CONF(8, 0);
+    else {
+        static arrol_device_flags lds_ok;
+        if (!arrol_allow_lds(token_conf_kernel<0>, static_cast<int>(sizeof(float) * 16384), lds_ok)) return ARROL_EHIP;
+        ARROL_CONF(0, sizeof(float) * d);
+    }
+#undef ARROL_CONF
     return arrol_launch_status();
 }
 
