@@ -129,6 +129,12 @@ def test_select_matches_rational_definition_random():
         live_def, order_def = definition_in_rationals(q_frac, K, Fraction(R, 1 << 30))
         live, order = O.select_group(k, K, R)
         assert live == live_def and order == order_def
+        # the batched entry point with this rho: two copies of the group, second one reversed
+        keep, surv = O.select(np.concatenate([q, q[::-1]]), 2, G, K, float(rho32))
+        assert [int(i) for i in surv[:K]] == live_def
+        live_rev, _ = definition_in_rationals(q_frac[::-1], K, Fraction(R, 1 << 30))
+        assert [int(i) - G for i in surv[K:]] == live_rev
+        assert keep.sum() == 2 * K and all(keep[i] for i in surv)
 
 
 def test_select_closed_form_closest_to_t():
@@ -1022,3 +1028,19 @@ def test_mlp_grad_dead_units_get_no_gradient():
     _, gW1, gb1, gw2, _ = O.score_mlp_ce_grad(hb, w1b, b1, w2, b2, y)
     assert np.all(gW1[1] == 0.0) and gb1[1] == 0.0 and gw2[1] == 0.0
     assert np.any(gW1[0] != 0.0)
+
+
+def test_grpo_objective_asymmetric_clip_range_hand_worked():
+    # eps_low = 0.1, eps_high = 0.3 (DAPO-style clip-higher): the range is [0.9, 1.3]
+    ratios = np.array([1.25, 1.5, 0.85, 0.95])
+    lp = np.log(ratios).astype(np.float32)
+    ratio = np.exp(lp.astype(np.float64))
+    adv = np.array([1.0, 1.0, -1.0, -1.0], dtype=np.float32)
+    e_lo, e_hi = float(np.float32(0.1)), float(np.float32(0.3))
+    J, grad, n_clip = O.grpo_objective(lp, np.zeros(4, dtype=np.float32), [0, 1, 2, 3, 4], adv, [0, 4],
+                                       eps_low=e_lo, eps_high=e_hi)
+    # 1.25 inside the range; 1.5 clipped at 1 + eps_high; 0.85 with A < 0: min(-0.85, -(1 - eps_low)) = -(1 - eps_low);
+    # 0.95 inside
+    terms = [ratio[0], 1.0 + e_hi, -(1.0 - e_lo), -ratio[3]]
+    assert abs(J - sum(terms) / 4) < 1e-15
+    assert n_clip == 2 and grad[1] == 0.0 and grad[2] == 0.0
