@@ -108,8 +108,8 @@ def test_llama1b_logprob_full_size_sampled_rows(A, W):
     torch.cuda.synchronize()
     rows = sample_rows(T, 150, cfg.vocab, targets)
     lp_o, lse_o = O.logprob(bits(hidden[rows.to(DEV)]), bits(lm_head), npy(targets)[rows.numpy()])
-    assert np.max(np.abs(npy(lp)[rows.numpy()] - lp_o)) < 2e-3
-    assert np.max(np.abs(npy(lse)[rows.numpy()] - lse_o)) < 2e-3
+    assert np.max(np.abs(npy(lp)[rows.numpy()] - lp_o)) < 1e-4      # the bar is 2e-3; 1e-4 is what fp32 accumulation allows here
+    assert np.max(np.abs(npy(lse)[rows.numpy()] - lse_o)) < 1e-4
     # whole output: finite, negative, and distributed as logits ~ N(0,1) imply (lse ~ log V + 1/2)
     assert bool(torch.isfinite(lp).all()) and float(lp.max()) <= 0.0
     assert abs(float(lse.mean()) - (np.log(cfg.vocab) + 0.5)) < 0.05
@@ -125,7 +125,7 @@ def test_logprob_other_model_geometries(A, W, name, T):
     torch.cuda.synchronize()
     rows = sample_rows(T, 40, cfg.vocab, targets)
     lp_o, _ = O.logprob(bits(hidden[rows.to(DEV)]), bits(lm_head), npy(targets)[rows.numpy()])
-    assert np.max(np.abs(npy(lp)[rows.numpy()] - lp_o)) < 2e-3
+    assert np.max(np.abs(npy(lp)[rows.numpy()] - lp_o)) < 1e-4
     assert bool(torch.isfinite(lp).all())
 
 

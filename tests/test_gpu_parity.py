@@ -13,6 +13,10 @@ pytestmark = pytest.mark.gpu
 
 PROB_TOL = 1e-3
 LOGP_TOL = 2e-3
+# what the arithmetic itself allows on the N(0,1) recipe (|logit| < ~8, d <= 4096): fp32 accumulation of exact
+# bf16 products ~ sqrt(d) * 2^-24 * |z| < 3e-5, exp/log of the fp32 sum ~ 2e-6, fp32 rounding of the result
+# ~ 1e-6.  Twenty times tighter than the bar, so that a small systematic error cannot hide under it.
+LOGP_DERIVED = 1e-4
 
 
 @pytest.fixture(scope="module")
@@ -211,7 +215,7 @@ def test_compact_out_of_range_indices_are_skipped(A, W):
 
 
 # ------------------------------------------------------------------------------- logprob
-def check_logprob(A, hidden, lm_head, targets, tol=LOGP_TOL):
+def check_logprob(A, hidden, lm_head, targets, tol=LOGP_DERIVED):
     lp, lse = A.arrol_logprob(hidden, lm_head, targets, want_lse=True)
     torch.cuda.synchronize()
     lp_o, lse_o = O.logprob(bits(hidden), bits(lm_head), npy(targets))
