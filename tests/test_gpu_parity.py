@@ -17,6 +17,9 @@ LOGP_TOL = 2e-3
 # bf16 products ~ sqrt(d) * 2^-24 * |z| < 3e-5, exp/log of the fp32 sum ~ 2e-6, fp32 rounding of the result
 # ~ 1e-6.  Twenty times tighter than the bar, so that a small systematic error cannot hide under it.
 LOGP_DERIVED = 1e-4
+# scores: one fp32 dot product of d <= 16k exact bf16 x fp32 products with |s| of order 1: ~ sqrt(d) * 2^-24 * |s|
+# < 2e-5; the sigmoid's slope is at most 1/4.  The bar (1e-3) stays as the second assertion.
+SCORE_DERIVED = 5e-5
 
 
 @pytest.fixture(scope="module")
@@ -49,6 +52,7 @@ def test_score_matches_oracle(A, n, d):
     s, q = A.arrol_score(hidden, w, bias=0.25)
     torch.cuda.synchronize()
     so, qo = O.score(bits(hidden), npy(w), 0.25)
+    assert np.max(np.abs(npy(s) - so)) < SCORE_DERIVED and np.max(np.abs(npy(q) - qo)) < SCORE_DERIVED / 4
     assert np.max(np.abs(npy(s) - so)) < 1e-3
     assert np.max(np.abs(npy(q) - qo)) < PROB_TOL
 
@@ -341,6 +345,7 @@ def test_score_mlp_matches_oracle(A, n, d, m):
     s_nb, _ = A.arrol_score_mlp(hidden, w1, None, w2)
     torch.cuda.synchronize()
     so, qo = O.score_mlp(bits(hidden), bits(w1), npy(b1), npy(w2), -0.125)
+    assert np.max(np.abs(npy(s) - so)) < SCORE_DERIVED and np.max(np.abs(npy(q) - qo)) < SCORE_DERIVED / 4
     assert np.max(np.abs(npy(s) - so)) < 1e-3 and np.max(np.abs(npy(q) - qo)) < PROB_TOL
     so_nb, _ = O.score_mlp(bits(hidden), bits(w1), np.zeros(m, np.float32), npy(w2), 0.0)
     assert np.max(np.abs(npy(s_nb) - so_nb)) < 1e-3
