@@ -19,7 +19,9 @@ def A():
 
 
 def random_probs(rng, n):
-    mode = rng.integers(0, 6)
+    mode = rng.integers(0, 7)
+    if mode == 6:
+        return (rng.integers(0, 64, n) * 0.5 * 2.0 ** -30).astype(np.float32)   # half-way between fixed-point codes
     if mode == 0:
         p = rng.random(n)
     elif mode == 1:
