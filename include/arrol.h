@@ -8,8 +8,13 @@
  *   arrol_compact        gather survivors' paged KV cache / tokens, re-batch  (Sec. 4.3 (i),(ii); Alg. 1)
  *   arrol_logprob        per-token log pi(o_t | o_<t) on the survivors        (Sec. 3 GRPO ratio; Sec. 4.3 (ii); Alg. 1)
  *   arrol_weighted_vote  rank-weighted answer vote for test-time scaling      (Sec. 4.4)
- * plus the paper's practical stochastic policy: arrol_histogram, arrol_calibrate, arrol_prune_bernoulli
- *                                                                               (App. A.4 Eq. 1-2; Alg. 1)
+ * plus, around them:
+ *   arrol_histogram, arrol_calibrate, arrol_prune_bernoulli   the paper's practical stochastic policy (App. A.4 Eq. 1-2; Alg. 1)
+ *   arrol_score_mlp                                            the 2-layer MLP form of the quality head (Sec. 4.2)
+ *   arrol_score_grad, arrol_score_mlp_grad, arrol_adamw_step  training the head on the fly (Sec. 4.2, 4.3 (iii); Alg. 1)
+ *   arrol_compact_inplace                                      hole-filling compaction of the same pool (Sec. 4.3 (i))
+ *   arrol_token_confidence, arrol_trace_confidence             trace confidence (Sec. 3)
+ *   arrol_grpo_advantage, arrol_grpo_objective                 group-relative advantage, clipped objective (Sec. 3)
  *
  * Conventions common to every call
  *   - Every data pointer is a DEVICE pointer owned by the caller (the library never
@@ -17,8 +22,10 @@
  *     its size comes from the matching *_workspace_bytes() query (a host computation).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
  *     enqueue kernels on it: no host synchronisation, no device-to-host copy.
- *   - Return value: ARROL_OK, or a negative ARROL_E* code.  Argument errors are detected
- *     on the host before anything is launched; on error nothing has been enqueued.
+ *   - Return value: ARROL_OK, or a negative ARROL_E* code.  Argument and workspace errors
+ *     (ARROL_EINVAL, ARROL_EWORKSPACE) are detected on the host before anything is launched:
+ *     nothing has been enqueued.  ARROL_EHIP means the runtime refused a launch; a call made
+ *     of several launches may then have enqueued the earlier ones, and its outputs are undefined.
  *   - Every kernel stays inside the buffers described here for ANY contents of the index
  *     arrays (out-of-range indices are skipped or clamped, see each call).
  */
