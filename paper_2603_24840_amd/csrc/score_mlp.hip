@@ -5,7 +5,8 @@
 // belong to one rollout and the reduction over hidden units is lane-local), bias + ReLU + the dot with w2
 // on the accumulators in registers; the [N, m] activations never reach memory.
 // Tile: 256 hidden units x 128 rollouts per workgroup pass, 4 wavefronts, each 2 x (32 units) x 128
-// rollouts; K chunks of 64 staged global -> registers -> LDS (two stages, XOR-swizzled 16-byte chunks).
+// rollouts; K chunks of 64 in XOR-swizzled 16-byte chunks, loaded global -> LDS directly into three stages
+// when d is a multiple of 64, else staged global -> registers -> LDS (two stages).
 //
 // arrol_score_mlp_grad: cross-entropy training gradient of the same head (Sec. 4.2, Sec. 4.3 (iii)).  The same
 // tile loop runs in two more modes:
@@ -28,7 +29,12 @@ constexpr int BK = 64;
 constexpr int TU = 2;     // 32-unit blocks per wave (unit rows c*128 + wave*32 + ...)
 constexpr int TR = 4;     // 32-rollout blocks per wave
 constexpr int kStageBytes = (BU + BR) * BK * 2;
-constexpr int kLdsBytes = 2 * kStageBytes;
+constexpr int kLdsBytes = 2 * kStageBytes;          // register-staged path: two stages
+constexpr int kRingStages = 3;                      // direct-to-LDS path: three stages, two of them in flight
+constexpr int kRingLdsBytes = kRingStages * kStageBytes;
+constexpr int kRingLoadsA = BU / 8 / 4;             // load instructions (8 rows x 128 bytes) per wave and stage
+constexpr int kRingLoadsB = BR / 8 / 4;
+constexpr int kRingLoads = kRingLoadsA + kRingLoadsB;
 constexpr int kPassA = BU * (BK / 8) / kThreads;   // 16-byte loads per thread for the W1 tile
 constexpr int kPassB = BR * (BK / 8) / kThreads;
 
@@ -54,10 +60,22 @@ struct MlpArgs {
     int kc_per_split;            // K chunks (of 64) per split
 };
 
-template <int MODE>
+template <int N>
+__device__ __forceinline__ void mlp_wait_vmcnt() {  // s_waitcnt vmcnt(N) only (gfx9 encoding), N <= 15
+    __builtin_amdgcn_s_waitcnt(0x0F70 | N);
+}
+
+// RING = false: any d (multiple of 8), K chunks staged global -> registers -> LDS, one chunk ahead.
+// RING = true (d a multiple of 64): K chunks go global -> LDS directly (no staging registers) into three
+// stages, two chunks ahead, so that a workgroup that is alone on its CU (few rollouts) still hides the
+// memory latency.  One instruction moves 8 tile rows x 128 bytes; lane l writes physical chunk l%8 of row
+// l/8, and fetches the logical chunk that the XOR swizzle stores there.
+template <int MODE, bool RING>
 __global__ __launch_bounds__(kThreads) void score_mlp_kernel(MlpArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    typedef __attribute__((address_space(3))) void* lds_ptr_t;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l31 = lane & 31, lh = lane >> 5;
     const int row0 = blockIdx.x * BR;
 
@@ -90,7 +108,8 @@ __global__ __launch_bounds__(kThreads) void score_mlp_kernel(MlpArgs a) {
         }
     }
 
-    uint4 stage[kPassA + kPassB];
+    constexpr int NSTAGE_REGS = RING ? 1 : kPassA + kPassB;
+    uint4 stage[NSTAGE_REGS];
     int ld_g = g0, ld_kc = 0;
     auto issue_loads = [&]() {
         const int k = (kc0 + ld_kc) * BK + ld_c * 8;
@@ -115,6 +134,58 @@ __global__ __launch_bounds__(kThreads) void score_mlp_kernel(MlpArgs a) {
         for (int p = 0; p < kPassB; ++p) *reinterpret_cast<uint4*>(sb + p * 32 * 128) = stage[kPassA + p];
     };
 
+    // ---- direct-to-LDS loader (RING) ---------------------------------------------------------------------
+    // wave w fetches A groups w*8 .. w*8+7 and B groups w*4 .. w*4+3 of every stage (a group = 8 tile rows)
+    const int rl_row = lane >> 3;                                     // row inside the group
+    constexpr int NPTR_A = RING ? kRingLoadsA : 1, NPTR_B = RING ? kRingLoadsB : 1;
+    const uint16_t* ring_a[NPTR_A];                                   // per lane: row base + logical chunk, k = 0
+    const uint16_t* ring_b[NPTR_B];
+    const unsigned lds0 = static_cast<unsigned>(reinterpret_cast<size_t>((lds_ptr_t)lds));
+    auto ring_point_a = [&](int grp) {                                // A rows of unit group `grp`
+#pragma unroll
+        for (int q = 0; q < NPTR_A; ++q) {
+            const int r = (wave * kRingLoadsA + q) * 8 + rl_row;      // tile row 0 .. 255
+            int u = grp * BU + r;
+            u = u < a.m ? u : a.m - 1;
+            const int logical = (lane & 7) ^ ((r >> 1) & 7);
+            ring_a[q] = a.w1 + static_cast<int64_t>(u) * a.a_stride + logical * 8;
+        }
+    };
+    if (RING) {
+#pragma unroll
+        for (int q = 0; q < NPTR_B; ++q) {
+            const int r = (wave * kRingLoadsB + q) * 8 + rl_row;      // tile row 0 .. 127
+            int row = row0 + r;
+            row = row < a.n_rows ? row : a.n_rows - 1;
+            const int64_t src = a.row_index ? a.row_index[row] : row;
+            const int logical = (lane & 7) ^ ((r >> 1) & 7);
+            ring_b[q] = a.hidden + src * a.row_stride + logical * 8;
+        }
+        ring_point_a(g0);
+    }
+    int ring_g = g0, ring_kc = 0, ring_buf = 0;
+    auto ring_issue = [&]() {                                         // the next chunk -> stage ring_buf
+        const int64_t k = static_cast<int64_t>(kc0 + ring_kc) * BK;
+        const unsigned dst_a = lds0 + ring_buf * kStageBytes + wave * kRingLoadsA * 1024;
+        const unsigned dst_b = lds0 + ring_buf * kStageBytes + BU * BK * 2 + wave * kRingLoadsB * 1024;
+#pragma unroll
+        for (int q = 0; q < NPTR_A; ++q) {
+            const uint16_t* src = ring_a[q] + k;
+            asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(dst_a + q * 1024) : "memory");
+        }
+#pragma unroll
+        for (int q = 0; q < NPTR_B; ++q) {
+            const uint16_t* src = ring_b[q] + k;
+            asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(dst_b + q * 1024) : "memory");
+        }
+        ring_buf = ring_buf + 1 == kRingStages ? 0 : ring_buf + 1;
+        if (++ring_kc == n_kc) {
+            ring_kc = 0;
+            ++ring_g;
+            ring_point_a(ring_g);        // rows of the next unit group (clamped: harmless past the last group)
+        }
+    };
+
     f32x16 acc[TU][TR];
 #pragma unroll
     for (int c = 0; c < TU; ++c)
@@ -125,15 +196,29 @@ __global__ __launch_bounds__(kThreads) void score_mlp_kernel(MlpArgs a) {
     float part[TR] = {0.f, 0.f, 0.f, 0.f};   // this lane's share of s for rollout row0 + j*32 + l31
 
     const int swz = (l31 >> 1) & 7;
-    issue_loads();
-    store_stage(0);
-    __syncthreads();
-    int g = g0, kc = 0;
+    if (RING) {
+        ring_issue();
+        if (total_it > 1) ring_issue();
+    } else {
+        issue_loads();
+        store_stage(0);
+        __syncthreads();
+    }
+    int g = g0, kc = 0, buf = 0;
     for (int it = 0; it < total_it; ++it) {
         const bool more = it + 1 < total_it;
-        if (more) issue_loads();
-        const unsigned char* sa = lds + (it & 1) * kStageBytes;
+        if (RING) {
+            // this wave's share of chunk `it` has landed (only the chunk after it may still be in flight) ...
+            if (more) mlp_wait_vmcnt<kRingLoads>(); else mlp_wait_vmcnt<0>();
+            // ... then so has everybody's, and nobody still reads the stage of chunk it-1, which chunk it+2 refills
+            __syncthreads();
+            if (it + 2 < total_it) ring_issue();
+        } else if (more) {
+            issue_loads();
+        }
+        const unsigned char* sa = lds + buf * kStageBytes;
         const unsigned char* sb = sa + BU * BK * 2;
+        buf = buf + 1 == (RING ? kRingStages : 2) ? 0 : buf + 1;
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
             const int coff = ((kk * 2 + lh) ^ swz) << 4;
@@ -150,8 +235,10 @@ __global__ __launch_bounds__(kThreads) void score_mlp_kernel(MlpArgs a) {
                 for (int j = 0; j < TR; ++j)
                     acc[c][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[c], fb[j], acc[c][j], 0, 0, 0);
         }
-        if (more) store_stage((it + 1) & 1);
-        __syncthreads();
+        if (!RING) {
+            if (more) store_stage(buf);
+            __syncthreads();
+        }
         if (++kc == n_kc) {
             // acc[c][j][v] belongs to A row (unit) g*BU + c*128 + wave*32 + (v/4)*8 + lh*4 + v%4 and B row
             // (rollout) row0 + j*32 + l31
@@ -212,6 +299,7 @@ __global__ __launch_bounds__(kThreads) void score_mlp_kernel(MlpArgs a) {
     // lane halves hold different units of the same rollout; then the four waves
 #pragma unroll
     for (int j = 0; j < TR; ++j) part[j] += __shfl_xor(part[j], 32, ARROL_WAVE);
+    if (RING) __syncthreads();                    // every wave has finished reading the last stage
     float* red = reinterpret_cast<float*>(lds);   // [4 waves][BR]
     if (lh == 0) {
 #pragma unroll
@@ -320,9 +408,14 @@ GradPlan make_grad_plan(int n_rows, int d, int m) {
 
 template <int MODE>
 int launch_mlp(const MlpArgs& a, dim3 grid, hipStream_t st) {
-    static arrol_device_flags lds_ok;
-    if (!arrol_allow_lds(&score_mlp_kernel<MODE>, kLdsBytes, lds_ok)) return ARROL_EHIP;
-    hipLaunchKernelGGL(score_mlp_kernel<MODE>, grid, dim3(kThreads), kLdsBytes, st, a);
+    static arrol_device_flags lds_ok, ring_ok;
+    if (a.d % BK == 0) {   // direct-to-LDS path
+        if (!arrol_allow_lds(&score_mlp_kernel<MODE, true>, kRingLdsBytes, ring_ok)) return ARROL_EHIP;
+        hipLaunchKernelGGL((score_mlp_kernel<MODE, true>), grid, dim3(kThreads), kRingLdsBytes, st, a);
+    } else {
+        if (!arrol_allow_lds(&score_mlp_kernel<MODE, false>, kLdsBytes, lds_ok)) return ARROL_EHIP;
+        hipLaunchKernelGGL((score_mlp_kernel<MODE, false>), grid, dim3(kThreads), kLdsBytes, st, a);
+    }
     return arrol_launch_status();
 }
 
