@@ -197,3 +197,15 @@ def test_bench_refuses_more_than_one_gpu():
     assert res.returncode == 2
     assert "ONE GPU" in res.stderr and "--gpus 2" in res.stderr
     assert res.stdout.strip() == ""
+
+
+def test_binding_argument_counts_match_the_header(pkg):
+    """Every prototype in include/arrol.h has as many parameters as its ctypes signature in the binding."""
+    from paper_2603_24840_amd import binding
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    protos = re.findall(r"\b(arrol_[a-z_]+)\s*\(([^;{]*?)\)\s*;", text, flags=re.S)
+    assert len(protos) == len(binding._SIGNATURES)
+    for name, params in protos:
+        params = " ".join(params.split())
+        n = 0 if params in ("", "void") else params.count(",") + 1
+        assert n == len(binding._SIGNATURES[name][1]), (name, n, len(binding._SIGNATURES[name][1]))
