@@ -27,7 +27,10 @@
  *     nothing has been enqueued.  ARROL_EHIP means the runtime refused a launch; a call made
  *     of several launches may then have enqueued the earlier ones, and its outputs are undefined.
  *   - Every kernel stays inside the buffers described here for ANY contents of the index
- *     arrays (out-of-range indices are skipped or clamped, see each call).
+ *     arrays whose range the call is told (block tables, survivor ids, targets, offsets:
+ *     out-of-range entries are skipped or clamped, see each call).  The one exception is
+ *     row_index of the scoring calls: the library is not told how many rows `hidden` holds,
+ *     so every row_index[i] must address a row of the caller's buffer.
  */
 #ifndef ARROL_H
 #define ARROL_H
