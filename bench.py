@@ -140,6 +140,20 @@ def time_extras(A, W, cfg, dev, torch, lp_hidden, lm_head, targets, cu, lws, rep
 
     out = {}
     N, d, T, V = cfg.n_rollouts, cfg.d, lp_hidden.shape[0], lm_head.shape[0]
+    # scoring at the test-time-scaling shape of the largest configuration (512 questions x 64 candidates,
+    # d = 4096): the one shape at which arrol_score is bandwidth- rather than launch-bound
+    big = W.CONFIGS["qwen8b"]
+    n_big = big.vote_q * big.vote_c
+    gb = torch.Generator(device=dev); gb.manual_seed(5)
+    h_big = W.randn_bf16((n_big, big.d), gb, dev)
+    w_big = torch.randn(big.d, generator=gb, device=dev) * big.d ** -0.5
+    s_big = torch.empty(n_big, device=dev)
+    q_big = torch.empty(n_big, device=dev)
+    ms = timed(lambda: A.arrol_score(h_big, w_big, 0.0, out_score=s_big, out_prob=q_big))
+    by = n_big * big.d * 2.0 + big.d * 4.0 + n_big * 8.0
+    out["score_test_time_shape"] = {"ms": ms, "shape": "N=%d, d=%d" % (n_big, big.d), "GBps": by / ms / 1e6,
+                                    "frac_of_hbm_peak": by / ms / 1e6 / HBM_PEAK_GBPS}
+    del h_big
     # stochastic policy (App. A.4): 4096-entry labelled buffer, 128 bins, then one Bernoulli prune of the batch
     s_buf, label, s_batch, uniforms = W.policy_inputs(cfg, dev)
     pol = A.Policy(0.5, 0.5, 0.5, 0.05, 0.95, 1.0)
@@ -341,6 +355,9 @@ def main():
                        "compact": (kv_bytes + meta_bytes) / stage_ms["compact"] / 1e6 if stage_ms["compact"] > 0 else 0.0},
         "logprob_tokens_per_s": T / lp_s if lp_s > 0 else 0.0,
         "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
+        "paper_context": "the paper reports no kernel-level number for this path; its end-to-end RLVR training "
+                         "speedup is 1.6-1.7x (up to 1.7x) on NVIDIA GH200 GPUs: other hardware, another metric, "
+                         "context only",
     }
     if args.inplace_compaction:
         # the in-place variant rewrites the pool, so the pool is restored (untimed) before every call
