@@ -124,6 +124,32 @@ def cpu_baseline(cfg, t, sample_rows, torch):
                                  "compact_bit_exact": compact_ok}}
 
 
+def time_score_test_time_shape(A, W, dev, torch, reps=10):
+    """arrol_score at the test-time-scaling shape of the largest configuration (512 questions x 64 candidates,
+    d = 4096): the one shape at which scoring is bandwidth- rather than launch-bound."""
+    big = W.CONFIGS["qwen8b"]
+    n_big = big.vote_q * big.vote_c
+    gb = torch.Generator(device=dev); gb.manual_seed(5)
+    h_big = W.randn_bf16((n_big, big.d), gb, dev)
+    w_big = torch.randn(big.d, generator=gb, device=dev) * big.d ** -0.5
+    s_big = torch.empty(n_big, device=dev)
+    q_big = torch.empty(n_big, device=dev)
+    run = lambda: A.arrol_score(h_big, w_big, 0.0, out_score=s_big, out_prob=q_big)
+    for _ in range(2):
+        run()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    by = n_big * big.d * 2.0 + big.d * 4.0 + n_big * 8.0
+    return {"bound": "hbm", "kernel": "score_reg_kernel at N=%d, d=%d (test-time scaling shape)" % (n_big, big.d),
+            "achieved": by / ms / 1e6, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": by / ms / 1e6 / HBM_PEAK_GBPS,
+            "ms": ms}
+
+
 def time_extras(A, W, cfg, dev, torch, lp_hidden, lm_head, targets, cu, lws, reps=10):
     """HIP-event timings of the calls that are not part of the five-stage step, at this workload's shapes.
     Each figure is the mean over `reps` back-to-back calls after two warm-up calls."""
@@ -140,20 +166,6 @@ def time_extras(A, W, cfg, dev, torch, lp_hidden, lm_head, targets, cu, lws, rep
 
     out = {}
     N, d, T, V = cfg.n_rollouts, cfg.d, lp_hidden.shape[0], lm_head.shape[0]
-    # scoring at the test-time-scaling shape of the largest configuration (512 questions x 64 candidates,
-    # d = 4096): the one shape at which arrol_score is bandwidth- rather than launch-bound
-    big = W.CONFIGS["qwen8b"]
-    n_big = big.vote_q * big.vote_c
-    gb = torch.Generator(device=dev); gb.manual_seed(5)
-    h_big = W.randn_bf16((n_big, big.d), gb, dev)
-    w_big = torch.randn(big.d, generator=gb, device=dev) * big.d ** -0.5
-    s_big = torch.empty(n_big, device=dev)
-    q_big = torch.empty(n_big, device=dev)
-    ms = timed(lambda: A.arrol_score(h_big, w_big, 0.0, out_score=s_big, out_prob=q_big))
-    by = n_big * big.d * 2.0 + big.d * 4.0 + n_big * 8.0
-    out["score_test_time_shape"] = {"ms": ms, "shape": "N=%d, d=%d" % (n_big, big.d), "GBps": by / ms / 1e6,
-                                    "frac_of_hbm_peak": by / ms / 1e6 / HBM_PEAK_GBPS}
-    del h_big
     # stochastic policy (App. A.4): 4096-entry labelled buffer, 128 bins, then one Bernoulli prune of the batch
     s_buf, label, s_batch, uniforms = W.policy_inputs(cfg, dev)
     pol = A.Policy(0.5, 0.5, 0.5, 0.05, 0.95, 1.0)
@@ -381,6 +393,8 @@ def main():
         result["compact_inplace"] = {"ms": ms, "pages_live": int(iout["n_pages_used"][0]), "pages_moved": moved,
                                      "bytes_read_plus_written": moved_bytes, "GBps": moved_bytes / ms / 1e6,
                                      "frac_of_hbm_peak": moved_bytes / ms / 1e6 / HBM_PEAK_GBPS}
+    if not only:
+        result["roofline_score"] = time_score_test_time_shape(A, W, dev, torch)
     if args.extras:
         result["extras"] = time_extras(A, W, cfg, dev, torch, lp_hidden, lm_head, targets, cu, lws)
     if not args.skip_cpu_baseline and not only:
