@@ -3,6 +3,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <atomic>
+#include <tuple>
+#include <type_traits>
+#include <utility>
 #include "arrol.h"
 
 #define ARROL_WAVE 64
@@ -10,8 +13,37 @@
 // 16-byte native vector (the nontemporal builtins need a native vector, not HIP's uint4 class)
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
+// Kernel launches go through arrol_launch(), which keeps the runtime's OWN return value of each launch
+// (hipLaunchKernel) in a per-thread slot: an error some earlier, unrelated HIP call of the caller left in
+// the thread's sticky error state is neither reported as a failure of this library nor cleared from the
+// caller's view.  arrol_launch_failed() peeks at the slot between the launches of one entry point;
+// arrol_launch_status() turns it into the entry point's return code and empties it.
+inline hipError_t& arrol_launch_error_slot() {
+    static thread_local hipError_t err = hipSuccess;
+    return err;
+}
+template <class Tuple, size_t... I>
+static inline hipError_t arrol_launch_packed(const void* fn, dim3 grid, dim3 block, size_t lds, hipStream_t st,
+                                             Tuple& vals, std::index_sequence<I...>) {
+    void* ptrs[] = {static_cast<void*>(&std::get<I>(vals))..., nullptr};
+    return hipLaunchKernel(fn, grid, block, ptrs, lds, st);
+}
+template <class... KArgs, class... Args>
+static inline void arrol_launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds, hipStream_t st,
+                                Args&&... args) {
+    static_assert(sizeof...(KArgs) == sizeof...(Args), "one argument per kernel parameter");
+    hipError_t& slot = arrol_launch_error_slot();
+    if (slot != hipSuccess) return;   // an earlier launch of this entry point failed: enqueue nothing more
+    std::tuple<std::remove_cv_t<KArgs>...> vals(static_cast<KArgs>(args)...);
+    slot = arrol_launch_packed(reinterpret_cast<const void*>(kernel), grid, block, lds, st, vals,
+                               std::index_sequence_for<KArgs...>{});
+}
+static inline bool arrol_launch_failed() { return arrol_launch_error_slot() != hipSuccess; }
 static inline int arrol_launch_status() {
-    return hipGetLastError() == hipSuccess ? ARROL_OK : ARROL_EHIP;
+    hipError_t& slot = arrol_launch_error_slot();
+    const bool ok = slot == hipSuccess;
+    slot = hipSuccess;
+    return ok ? ARROL_OK : ARROL_EHIP;
 }
 
 // Raises a kernel's dynamic-LDS limit once per device (function attributes are per device); `bytes` is the

@@ -266,7 +266,7 @@ extern "C" int arrol_compact(const void* kv_src, arrol_kv_layout src, void* kv_d
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (n_keep < 0 || n_src < 0 || !n_pages_used) return ARROL_EINVAL;
     if (n_keep == 0) {
-        hipLaunchKernelGGL(compact_empty_kernel, dim3(1), dim3(1), 0, st, n_pages_used);
+        arrol_launch(compact_empty_kernel, dim3(1), dim3(1), 0, st, n_pages_used);
         return arrol_launch_status();
     }
     if (!same_geometry(src, dst) || src.n_layers < 1 || src.page_tokens < 1 || src.n_kv_heads < 1 ||
@@ -292,11 +292,11 @@ extern "C" int arrol_compact(const void* kv_src, arrol_kv_layout src, void* kv_d
     const int64_t blocks = kv_blocks + (with_tokens && max_len > 0 ? n_keep : 0);
     if (blocks > INT32_MAX) return ARROL_EINVAL;
     int32_t* base = static_cast<int32_t*>(workspace);
-    hipLaunchKernelGGL(compact_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, survivor_idx, seq_len_src, n_src,
+    arrol_launch(compact_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, survivor_idx, seq_len_src, n_src,
                        n_keep, src.page_tokens, max_pages_per_seq, base, block_table_dst, seq_len_dst, src_of_dst,
                        n_pages_used);
-    if (hipGetLastError() != hipSuccess) return ARROL_EHIP;
-    hipLaunchKernelGGL(compact_copy_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kCopyThreads), 0, st,
+    if (arrol_launch_failed()) return arrol_launch_status();
+    arrol_launch(compact_copy_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kCopyThreads), 0, st,
                        static_cast<const u32x4*>(kv_src), static_cast<u32x4*>(kv_dst), chunk_bytes / 16,
                        src.n_pages, dst.n_pages, block_table_src, survivor_idx, base, n_src, n_keep,
                        max_pages_per_seq, kv_blocks, tokens_src, tokens_dst, max_len);
@@ -336,24 +336,24 @@ extern "C" int arrol_compact_inplace(void* kv, arrol_kv_layout layout, const int
     int32_t* mover_list = hole_list + P;
     int32_t* counters = mover_list + P;
     if (P > 0) {
-        hipLaunchKernelGGL(inplace_clear_kernel, dim3(static_cast<unsigned>((P + 255) / 256)), dim3(256), 0, st, live, P);
-        if (hipGetLastError() != hipSuccess) return ARROL_EHIP;
+        arrol_launch(inplace_clear_kernel, dim3(static_cast<unsigned>((P + 255) / 256)), dim3(256), 0, st, live, P);
+        if (arrol_launch_failed()) return arrol_launch_status();
     }
     if (slots > 0) {
-        hipLaunchKernelGGL(inplace_mark_kernel, dim3(static_cast<unsigned>((slots + 255) / 256)), dim3(256), 0, st,
+        arrol_launch(inplace_mark_kernel, dim3(static_cast<unsigned>((slots + 255) / 256)), dim3(256), 0, st,
                            survivor_idx, seq_len_src, block_table_src, n_src, n_keep, layout.page_tokens,
                            max_pages_per_seq, P, live, seq_len_dst, src_of_dst);
-        if (hipGetLastError() != hipSuccess) return ARROL_EHIP;
+        if (arrol_launch_failed()) return arrol_launch_status();
     }
-    hipLaunchKernelGGL(inplace_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, live, P, new_page, hole_list,
+    arrol_launch(inplace_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, live, P, new_page, hole_list,
                        mover_list, counters, n_pages_used, n_moved);
-    if (hipGetLastError() != hipSuccess) return ARROL_EHIP;
+    if (arrol_launch_failed()) return arrol_launch_status();
     const int64_t m_bound = slots < P ? slots : P;   // no more movers than survivor pages or pool pages
     const int64_t kv_blocks = m_bound * layout.n_layers * 2;
     const int64_t blocks = kv_blocks + n_keep;
     if (blocks > INT32_MAX) return ARROL_EINVAL;
     if (blocks == 0) return ARROL_OK;
-    hipLaunchKernelGGL(inplace_copy_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kCopyThreads), 0, st,
+    arrol_launch(inplace_copy_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kCopyThreads), 0, st,
                        static_cast<u32x4*>(kv), chunk_bytes / 16, P, hole_list, mover_list, counters,
                        m_bound > 0 ? m_bound : 1, kv_blocks, new_page, survivor_idx, seq_len_src, block_table_src,
                        n_src, layout.page_tokens, max_pages_per_seq, block_table_dst);

@@ -282,15 +282,15 @@ extern "C" int arrol_token_confidence(const void* hidden, const void* lm_head, c
     const int nb = colsum_blocks(V);
     float* colsum = static_cast<float*>(workspace);
     float* partial = colsum + d;
-    hipLaunchKernelGGL(colsum_partial_kernel, dim3(nb), dim3(kColThreads), 0, st,
+    arrol_launch(colsum_partial_kernel, dim3(nb), dim3(kColThreads), 0, st,
                        static_cast<const u32x4*>(lm_head), V, d / 8, partial);
-    hipLaunchKernelGGL(reduce_rows_f32_kernel<0>, dim3((d + 31) / 32), dim3(256), 0, st, partial, nb,
+    arrol_launch(reduce_rows_f32_kernel<0>, dim3((d + 31) / 32), dim3(256), 0, st, partial, nb,
                        static_cast<int64_t>(d), static_cast<int64_t>(d), 1.f, colsum);
     const int64_t blocks_needed = (T + kConfWaves - 1) / kConfWaves;
     const int grid = static_cast<int>(blocks_needed < 256 * 8 ? blocks_needed : 256 * 8);
     const u32x4* h = static_cast<const u32x4*>(hidden);
     const int chunks = (d / 8 + ARROL_WAVE - 1) / ARROL_WAVE;
-#define ARROL_CONF(CH, LDS) hipLaunchKernelGGL(token_conf_kernel<CH>, dim3(grid), dim3(kConfThreads), LDS, st, h, colsum, lse, T, V, d / 8, conf_out)
+#define ARROL_CONF(CH, LDS) arrol_launch(token_conf_kernel<CH>, dim3(grid), dim3(kConfThreads), LDS, st, h, colsum, lse, T, V, d / 8, conf_out)
     if (chunks <= 1) ARROL_CONF(1, 0);
     else if (chunks <= 2) ARROL_CONF(2, 0);
     else if (chunks <= 4) ARROL_CONF(4, 0);
@@ -320,7 +320,7 @@ extern "C" int arrol_trace_confidence(const float* conf, const int64_t* cu_seqle
         return ARROL_EWORKSPACE;
     double* prefix = static_cast<double*>(workspace);
     uint64_t* keys = reinterpret_cast<uint64_t*>(prefix + T + n_seq);
-    hipLaunchKernelGGL(trace_conf_kernel, dim3(n_seq), dim3(kAggThreads), 0, static_cast<hipStream_t>(stream), conf,
+    arrol_launch(trace_conf_kernel, dim3(n_seq), dim3(kAggThreads), 0, static_cast<hipStream_t>(stream), conf,
                        cu_seqlens, T, window, bottom_percent, prefix, keys, mean_out, min_out, bottom_out);
     return arrol_launch_status();
 }

@@ -124,7 +124,7 @@ extern "C" int arrol_grpo_advantage(const float* reward, const int64_t* group_of
     if (N < 0 || n_groups < 0 || (ddof != 0 && ddof != 1) || !(eps >= 0.f)) return ARROL_EINVAL;
     if (n_groups == 0 || N == 0) return ARROL_OK;
     if (!reward || !group_offsets || !advantage) return ARROL_EINVAL;
-    hipLaunchKernelGGL(grpo_advantage_kernel, dim3(n_groups), dim3(ARROL_WAVE), 0, static_cast<hipStream_t>(stream),
+    arrol_launch(grpo_advantage_kernel, dim3(n_groups), dim3(ARROL_WAVE), 0, static_cast<hipStream_t>(stream),
                        reward, group_offsets, N, n_groups, ddof, static_cast<double>(eps), advantage, seq_weight);
     return arrol_launch_status();
 }
@@ -141,7 +141,7 @@ extern "C" int arrol_grpo_objective(const float* logp, const float* logp_ref, co
         return ARROL_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (n_seq == 0) {
-        hipLaunchKernelGGL(grpo_finish_kernel, dim3(1), dim3(kObjThreads), 0, st, nullptr, nullptr, 0, objective_out,
+        arrol_launch(grpo_finish_kernel, dim3(1), dim3(kObjThreads), 0, st, nullptr, nullptr, 0, objective_out,
                            n_clipped);
         return arrol_launch_status();
     }
@@ -150,10 +150,10 @@ extern "C" int arrol_grpo_objective(const float* logp, const float* logp_ref, co
         return ARROL_EWORKSPACE;
     double* partial = static_cast<double*>(workspace);
     int64_t* clipped = reinterpret_cast<int64_t*>(partial + n_seq);
-    hipLaunchKernelGGL(grpo_objective_kernel, dim3(n_seq), dim3(kObjThreads), 0, st, logp, logp_ref, cu_seqlens, T,
+    arrol_launch(grpo_objective_kernel, dim3(n_seq), dim3(kObjThreads), 0, st, logp, logp_ref, cu_seqlens, T,
                        advantage, seq_weight, static_cast<double>(eps_low), static_cast<double>(eps_high),
                        static_cast<double>(beta), grad_logp, partial, clipped);
-    hipLaunchKernelGGL(grpo_finish_kernel, dim3(1), dim3(kObjThreads), 0, st, partial, clipped, n_seq, objective_out,
+    arrol_launch(grpo_finish_kernel, dim3(1), dim3(kObjThreads), 0, st, partial, clipped, n_seq, objective_out,
                        n_clipped);
     return arrol_launch_status();
 }

@@ -637,11 +637,11 @@ extern "C" int arrol_logprob(const void* hidden, const void* lm_head, const int3
     a.n_tb = p.n_tb; a.n_sp = p.n_sp; a.n_vt = p.n_vt;
     const int tb_pad = (p.n_tb + kXcds - 1) / kXcds * kXcds;
     if (d % 64 == 0 && !g_force_general)
-        hipLaunchKernelGGL(logprob_ring_kernel<FastTile>, dim3(tb_pad * p.n_sp), dim3(FastTile::NT), FastTile::LDS_BYTES, st, a);
+        arrol_launch(logprob_ring_kernel<FastTile>, dim3(tb_pad * p.n_sp), dim3(FastTile::NT), FastTile::LDS_BYTES, st, a);
     else
-        hipLaunchKernelGGL(logprob_kernel<MainTile>, dim3(tb_pad * p.n_sp), dim3(MainTile::NT), MainTile::LDS_BYTES, st, a);
-    if (hipGetLastError() != hipSuccess) return ARROL_EHIP;
-    hipLaunchKernelGGL(logprob_finalize_kernel, dim3(static_cast<unsigned>((T + 255) / 256)), dim3(256), 0, st,
+        arrol_launch(logprob_kernel<MainTile>, dim3(tb_pad * p.n_sp), dim3(MainTile::NT), MainTile::LDS_BYTES, st, a);
+    if (arrol_launch_failed()) return arrol_launch_status();
+    arrol_launch(logprob_finalize_kernel, dim3(static_cast<unsigned>((T + 255) / 256)), dim3(256), 0, st,
                        static_cast<const float*>(workspace), targets, T, V, p.n_sp, logprob_out, lse_out);
     return arrol_launch_status();
 }

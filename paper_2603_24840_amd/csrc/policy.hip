@@ -148,12 +148,12 @@ extern "C" int arrol_histogram(const float* s_norm, const uint8_t* label, int64_
     if (M < 0 || B < 1 || B > kMaxBins || !c_pos || !c_neg) return ARROL_EINVAL;
     if (M > 0 && (!s_norm || !label)) return ARROL_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    hipLaunchKernelGGL(zero_counts_kernel, dim3((B + 255) / 256), dim3(256), 0, st, c_pos, c_neg, B);
-    if (hipGetLastError() != hipSuccess) return ARROL_EHIP;
+    arrol_launch(zero_counts_kernel, dim3((B + 255) / 256), dim3(256), 0, st, c_pos, c_neg, B);
+    if (arrol_launch_failed()) return arrol_launch_status();
     if (M == 0) return ARROL_OK;
     int64_t blocks = (M + kHistThreads * 16 - 1) / (kHistThreads * 16);
     blocks = blocks < 1 ? 1 : (blocks > 1024 ? 1024 : blocks);
-    hipLaunchKernelGGL(histogram_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kHistThreads),
+    arrol_launch(histogram_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kHistThreads),
                        2 * B * sizeof(unsigned int), st, s_norm, label, M, B,
                        reinterpret_cast<unsigned long long*>(c_pos), reinterpret_cast<unsigned long long*>(c_neg));
     return arrol_launch_status();
@@ -162,7 +162,7 @@ extern "C" int arrol_histogram(const float* s_norm, const uint8_t* label, int64_
 extern "C" int arrol_calibrate(const int64_t* c_pos, const int64_t* c_neg, int32_t B, arrol_policy pol,
                                float* q_lut, float* p_lut, double* delta, void* stream) {
     if (B < 1 || B > kMaxBins || !c_pos || !c_neg || !q_lut || !p_lut || !policy_ok(pol)) return ARROL_EINVAL;
-    hipLaunchKernelGGL(calibrate_kernel, dim3(1), dim3(kCalThreads), 0, static_cast<hipStream_t>(stream), c_pos,
+    arrol_launch(calibrate_kernel, dim3(1), dim3(kCalThreads), 0, static_cast<hipStream_t>(stream), c_pos,
                        c_neg, B, pol, q_lut, p_lut, delta);
     return arrol_launch_status();
 }
@@ -172,7 +172,7 @@ extern "C" int arrol_prune_bernoulli(const float* s_norm, const float* uniforms,
                                      int32_t* n_survivors, void* stream) {
     if (N < 0 || B < 1 || B > kMaxBins || !p_lut || !n_survivors) return ARROL_EINVAL;
     if (N > 0 && (!s_norm || !uniforms || !keep_mask || !survivor_idx)) return ARROL_EINVAL;
-    hipLaunchKernelGGL(prune_bernoulli_kernel, dim3(1), dim3(kPruneThreads), 0, static_cast<hipStream_t>(stream),
+    arrol_launch(prune_bernoulli_kernel, dim3(1), dim3(kPruneThreads), 0, static_cast<hipStream_t>(stream),
                        s_norm, uniforms, N, p_lut, B, p_out, keep_mask, survivor_idx, n_survivors);
     return arrol_launch_status();
 }

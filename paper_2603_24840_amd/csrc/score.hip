@@ -144,18 +144,18 @@ extern "C" int arrol_score(const void* hidden, int64_t row_stride_elems, const i
     if (chunks <= 8) {
         const u32x4* h = static_cast<const u32x4*>(hidden);
         const int64_t rs = row_stride_elems / 8;
-#define ARROL_SCORE_REG(CH) hipLaunchKernelGGL(score_reg_kernel<CH>, dim3(grid), dim3(kScoreThreads), 0, st, h, rs, row_index, w, bias, n_rows, d / 8, score_out, prob_out)
+#define ARROL_SCORE_REG(CH) arrol_launch(score_reg_kernel<CH>, dim3(grid), dim3(kScoreThreads), 0, st, h, rs, row_index, w, bias, n_rows, d / 8, score_out, prob_out)
         if (chunks <= 1) ARROL_SCORE_REG(1);
         else if (chunks <= 2) ARROL_SCORE_REG(2);
         else if (chunks <= 4) ARROL_SCORE_REG(4);
         else ARROL_SCORE_REG(8);
 #undef ARROL_SCORE_REG
     } else if (d <= kScoreLdsFloats) {
-        hipLaunchKernelGGL(score_kernel<true>, dim3(grid), dim3(kScoreThreads), sizeof(float) * d, st,
+        arrol_launch(score_kernel<true>, dim3(grid), dim3(kScoreThreads), sizeof(float) * d, st,
                            static_cast<const u32x4*>(hidden), row_stride_elems / 8, row_index, w, bias,
                            n_rows, d / 8, score_out, prob_out);
     } else {
-        hipLaunchKernelGGL(score_kernel<false>, dim3(grid), dim3(kScoreThreads), 0, st,
+        arrol_launch(score_kernel<false>, dim3(grid), dim3(kScoreThreads), 0, st,
                            static_cast<const u32x4*>(hidden), row_stride_elems / 8, row_index, w, bias,
                            n_rows, d / 8, score_out, prob_out);
     }

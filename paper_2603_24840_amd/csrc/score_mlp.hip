@@ -411,10 +411,10 @@ int launch_mlp(const MlpArgs& a, dim3 grid, hipStream_t st) {
     static arrol_device_flags lds_ok, ring_ok;
     if (a.d % BK == 0) {   // direct-to-LDS path
         if (!arrol_allow_lds(&score_mlp_kernel<MODE, true>, kRingLdsBytes, ring_ok)) return ARROL_EHIP;
-        hipLaunchKernelGGL((score_mlp_kernel<MODE, true>), grid, dim3(kThreads), kRingLdsBytes, st, a);
+        arrol_launch((score_mlp_kernel<MODE, true>), grid, dim3(kThreads), kRingLdsBytes, st, a);
     } else {
         if (!arrol_allow_lds(&score_mlp_kernel<MODE, false>, kLdsBytes, lds_ok)) return ARROL_EHIP;
-        hipLaunchKernelGGL((score_mlp_kernel<MODE, false>), grid, dim3(kThreads), kLdsBytes, st, a);
+        arrol_launch((score_mlp_kernel<MODE, false>), grid, dim3(kThreads), kLdsBytes, st, a);
     }
     return arrol_launch_status();
 }
@@ -449,14 +449,14 @@ extern "C" int arrol_score_mlp_grad(const void* hidden, int64_t row_stride_elems
     if (n_rows == 0) {   // empty batch: zero loss and gradients
         hipStream_t s0 = static_cast<hipStream_t>(stream);
         const int64_t width = static_cast<int64_t>(m) * d;
-        hipLaunchKernelGGL(reduce_rows_f32_kernel<0>, dim3(static_cast<unsigned>((width + 31) / 32)), dim3(256), 0, s0,
+        arrol_launch(reduce_rows_f32_kernel<0>, dim3(static_cast<unsigned>((width + 31) / 32)), dim3(256), 0, s0,
                            nullptr, 0, width, width, 0.f, grad_w1);
-        hipLaunchKernelGGL(reduce_rows_f32_kernel<0>, dim3((m + 31) / 32), dim3(256), 0, s0, nullptr, 0,
+        arrol_launch(reduce_rows_f32_kernel<0>, dim3((m + 31) / 32), dim3(256), 0, s0, nullptr, 0,
                            static_cast<int64_t>(m), static_cast<int64_t>(m), 0.f, grad_b1);
-        hipLaunchKernelGGL(reduce_rows_f32_kernel<0>, dim3((m + 31) / 32), dim3(256), 0, s0, nullptr, 0,
+        arrol_launch(reduce_rows_f32_kernel<0>, dim3((m + 31) / 32), dim3(256), 0, s0, nullptr, 0,
                            static_cast<int64_t>(m), static_cast<int64_t>(m), 0.f, grad_w2);
-        if (loss_out) hipLaunchKernelGGL(reduce_rows_f32_kernel<0>, dim3(1), dim3(256), 0, s0, nullptr, 0, 1, 1, 0.f, loss_out);
-        if (grad_b2) hipLaunchKernelGGL(reduce_rows_f32_kernel<0>, dim3(1), dim3(256), 0, s0, nullptr, 0, 1, 1, 0.f, grad_b2);
+        if (loss_out) arrol_launch(reduce_rows_f32_kernel<0>, dim3(1), dim3(256), 0, s0, nullptr, 0, 1, 1, 0.f, loss_out);
+        if (grad_b2) arrol_launch(reduce_rows_f32_kernel<0>, dim3(1), dim3(256), 0, s0, nullptr, 0, 1, 1, 0.f, grad_b2);
         return arrol_launch_status();
     }
     if (!hidden || !w1 || !w2 || !labels || !arrol_aligned16(hidden) || !arrol_aligned16(w1)) return ARROL_EINVAL;
@@ -479,18 +479,18 @@ extern "C" int arrol_score_mlp_grad(const void* hidden, int64_t row_stride_elems
     a.n_rows = n_rows; a.d = d; a.m = m; a.score_out = score; a.prob_out = prob;
     int rc = launch_mlp<kForward>(a, dim3(p.n_rb), st);
     if (rc != ARROL_OK) return rc;
-    hipLaunchKernelGGL(mlp_residual_kernel, dim3(1), dim3(1024), 0, st, score, prob, labels, n_rows, resid, loss_out,
+    arrol_launch(mlp_residual_kernel, dim3(1), dim3(1024), 0, st, score, prob, labels, n_rows, resid, loss_out,
                        grad_b2);
     // delta^T and the per-unit sums
     a.resid = resid; a.delta_t = dt; a.delta_stride = p.n_pad; a.unit_partial = unit;
     rc = launch_mlp<kDelta>(a, dim3(p.n_rb), st);
     if (rc != ARROL_OK) return rc;
-    hipLaunchKernelGGL(reduce_rows_f32_kernel<0>, dim3((m + 31) / 32), dim3(256), 0, st, unit, p.n_rb,
+    arrol_launch(reduce_rows_f32_kernel<0>, dim3((m + 31) / 32), dim3(256), 0, st, unit, p.n_rb,
                        static_cast<int64_t>(2) * m, static_cast<int64_t>(m), 1.f, grad_w2);
-    hipLaunchKernelGGL(reduce_rows_f32_kernel<0>, dim3((m + 31) / 32), dim3(256), 0, st, unit + m, p.n_rb,
+    arrol_launch(reduce_rows_f32_kernel<0>, dim3((m + 31) / 32), dim3(256), 0, st, unit + m, p.n_rb,
                        static_cast<int64_t>(2) * m, static_cast<int64_t>(m), 1.f, grad_b1);
     // H^T, then dL/dW1 = delta^T . H over the rollouts
-    hipLaunchKernelGGL(mlp_transpose_kernel, dim3(p.n_pad / 64, (d + 63) / 64), dim3(256), 0, st,
+    arrol_launch(mlp_transpose_kernel, dim3(p.n_pad / 64, (d + 63) / 64), dim3(256), 0, st,
                        static_cast<const uint16_t*>(hidden), row_stride_elems, row_index, n_rows, d, p.n_pad, ht);
     MlpArgs g = {};
     g.hidden = ht; g.row_stride = p.n_pad; g.row_index = nullptr;
@@ -501,7 +501,7 @@ extern "C" int arrol_score_mlp_grad(const void* hidden, int64_t row_stride_elems
     if (rc != ARROL_OK) return rc;
     if (p.splits > 1) {
         const int64_t width = static_cast<int64_t>(m) * d;
-        hipLaunchKernelGGL(reduce_rows_f32_kernel<0>, dim3(static_cast<unsigned>((width + 31) / 32)), dim3(256), 0, st,
+        arrol_launch(reduce_rows_f32_kernel<0>, dim3(static_cast<unsigned>((width + 31) / 32)), dim3(256), 0, st,
                            slab, p.splits, width, width, 1.f, grad_w1);
     }
     return arrol_launch_status();

@@ -49,7 +49,7 @@ extern "C" int arrol_select(const float* prob, int32_t n_groups, int32_t G, int3
     if (!prob || !keep_mask || !survivor_idx) return ARROL_EINVAL;
     const int64_t R = static_cast<int64_t>(rintf(rho * 1073741824.0f));
     const int grid = (n_groups + kGroupsPerBlock - 1) / kGroupsPerBlock;
-    hipLaunchKernelGGL(select_kernel, dim3(grid), dim3(kSelectThreads), 0, static_cast<hipStream_t>(stream),
+    arrol_launch(select_kernel, dim3(grid), dim3(kSelectThreads), 0, static_cast<hipStream_t>(stream),
                        prob, n_groups, G, K, R, keep_mask, survivor_idx);
     return arrol_launch_status();
 }

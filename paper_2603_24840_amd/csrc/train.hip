@@ -185,7 +185,7 @@ int launch_grad(int grid, size_t lds_bytes, hipStream_t st, const void* hidden, 
     static arrol_device_flags lds_ok;
     if (!arrol_allow_lds(score_grad_kernel<CH>, static_cast<int>(sizeof(float) * (kGradMaxD + kGradWaves * 512)), lds_ok))
         return ARROL_EHIP;
-    hipLaunchKernelGGL(score_grad_kernel<CH>, dim3(grid), dim3(kGradThreads), lds_bytes, st,
+    arrol_launch(score_grad_kernel<CH>, dim3(grid), dim3(kGradThreads), lds_bytes, st,
                        static_cast<const u32x4*>(hidden), row_stride_vec, row_index, w, bias, labels, n_rows, d_vec,
                        partial, tail);
     return arrol_launch_status();
@@ -208,7 +208,7 @@ extern "C" int arrol_score_grad(const void* hidden, int64_t row_stride_elems, co
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int col_blocks = (d + 255) / 256;
     if (n_rows == 0) {   // empty batch: zero loss and gradients
-        hipLaunchKernelGGL(score_grad_reduce_kernel, dim3(col_blocks + 1), dim3(256), 0, st, nullptr, nullptr, 0, d,
+        arrol_launch(score_grad_reduce_kernel, dim3(col_blocks + 1), dim3(256), 0, st, nullptr, nullptr, 0, d,
                            0.f, loss_out, grad_w, grad_bias);
         return arrol_launch_status();
     }
@@ -228,7 +228,7 @@ extern "C" int arrol_score_grad(const void* hidden, int64_t row_stride_elems, co
     else if (chunks <= 8) rc = launch_grad<8>(grid, lds_bytes, st, hidden, rsv, row_index, w, bias, labels, n_rows, d_vec, partial, tail);
     else rc = launch_grad<16>(grid, lds_bytes, st, hidden, rsv, row_index, w, bias, labels, n_rows, d_vec, partial, tail);
     if (rc != ARROL_OK) return rc;
-    hipLaunchKernelGGL(score_grad_reduce_kernel, dim3(col_blocks + 1), dim3(256), 0, st, partial, tail, grid, d,
+    arrol_launch(score_grad_reduce_kernel, dim3(col_blocks + 1), dim3(256), 0, st, partial, tail, grid, d,
                        1.f / static_cast<float>(n_rows), loss_out, grad_w, grad_bias);
     return arrol_launch_status();
 }
@@ -244,7 +244,7 @@ extern "C" int arrol_adamw_step(float* param, const float* grad, float* m, float
     const double bc2 = 1.0 - __builtin_pow(static_cast<double>(beta2), static_cast<double>(step));
     int64_t blocks = (n + 255) / 256;
     if (blocks > 256 * 16) blocks = 256 * 16;
-    hipLaunchKernelGGL(adamw_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0,
+    arrol_launch(adamw_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0,
                        static_cast<hipStream_t>(stream), param, grad, m, v, n, lr, beta1, beta2, eps, weight_decay,
                        static_cast<float>(1.0 / bc1), static_cast<float>(1.0 / bc2),
                        static_cast<uint16_t*>(param_bf16));

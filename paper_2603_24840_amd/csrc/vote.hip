@@ -56,7 +56,7 @@ extern "C" int arrol_weighted_vote(const float* prob, const int32_t* answer_id, 
     if (n_questions == 0) return ARROL_OK;
     if (!prob || !answer_id || !winner) return ARROL_EINVAL;
     const int grid = (n_questions + kQuestionsPerBlock - 1) / kQuestionsPerBlock;
-    hipLaunchKernelGGL(vote_kernel, dim3(grid), dim3(kVoteThreads), 0, static_cast<hipStream_t>(stream),
+    arrol_launch(vote_kernel, dim3(grid), dim3(kVoteThreads), 0, static_cast<hipStream_t>(stream),
                        prob, answer_id, n_questions, C, n_answers, winner, tally);
     return arrol_launch_status();
 }
