@@ -13,6 +13,7 @@
  *   arrol_score_mlp                                            the 2-layer MLP form of the quality head (Sec. 4.2)
  *   arrol_score_grad, arrol_score_mlp_grad, arrol_adamw_step  training the head on the fly (Sec. 4.2, 4.3 (iii); Alg. 1)
  *   arrol_compact_inplace                                      hole-filling compaction of the same pool (Sec. 4.3 (i))
+ *   arrol_compact_static                                       arrol_compact without a workspace argument (fixed scratch)
  *   arrol_token_confidence, arrol_trace_confidence             trace confidence (Sec. 3)
  *   arrol_grpo_advantage, arrol_grpo_objective                 group-relative advantage, clipped objective (Sec. 3)
  *
@@ -136,6 +137,25 @@ int arrol_compact(const void* kv_src, arrol_kv_layout src, void* kv_dst, arrol_k
                   int32_t* block_table_dst, int32_t* seq_len_dst, int32_t* tokens_dst,
                   int32_t* src_of_dst, int64_t* n_pages_used,
                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * arrol_compact for callers that cannot allocate or pass scratch memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the same operation with the same arguments,
+ * outputs and error rules as arrol_compact, minus the workspace.  The per-survivor base offsets live in
+ * a fixed device array inside the library (ARROL_COMPACT_STATIC_MAX_KEEP + 1 int32 = 64 KiB, held by
+ * every GPU the library runs on until the process ends); the call allocates and frees nothing.
+ * n_keep > ARROL_COMPACT_STATIC_MAX_KEEP returns ARROL_EWORKSPACE with nothing enqueued; ARROL_EHIP if
+ * the array's device address cannot be obtained (looked up once per device, on the first call there).
+ * All calls on one GPU share that array: two calls whose kernels may overlap on the same GPU (different
+ * streams, or several host threads) race - serialise them, or use arrol_compact with separate workspaces.
+ */
+#define ARROL_COMPACT_STATIC_MAX_KEEP 16383
+int arrol_compact_static(const void* kv_src, arrol_kv_layout src, void* kv_dst, arrol_kv_layout dst,
+                         const int32_t* block_table_src, const int32_t* seq_len_src,
+                         int32_t max_pages_per_seq, const int32_t* tokens_src, int32_t max_len,
+                         const int32_t* survivor_idx, int32_t n_src, int32_t n_keep,
+                         int32_t* block_table_dst, int32_t* seq_len_dst, int32_t* tokens_dst,
+                         int32_t* src_of_dst, int64_t* n_pages_used, void* stream);
 
 /*
  * Stage 3, in-place variant ("hole filling").  Same paper passage: pruned requests leave the pool so that

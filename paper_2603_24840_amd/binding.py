@@ -55,6 +55,8 @@ _SIGNATURES = {
     "arrol_compact_workspace_bytes": (_sz, [_i32]),
     "arrol_compact": (ctypes.c_int, [_vp, KVLayout, _vp, KVLayout, _vp, _vp, _i32, _vp, _i32, _vp, _i32, _i32,
                                      _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "arrol_compact_static": (ctypes.c_int, [_vp, KVLayout, _vp, KVLayout, _vp, _vp, _i32, _vp, _i32, _vp, _i32, _i32,
+                                            _vp, _vp, _vp, _vp, _vp, _vp]),
     "arrol_compact_inplace_workspace_bytes": (_sz, [_i64]),
     "arrol_compact_inplace": (ctypes.c_int, [_vp, KVLayout, _vp, _vp, _i32, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp,
                                              _vp, _sz, _vp]),
@@ -296,6 +298,25 @@ def arrol_compact(kv_src, kv_dst, block_table_src, seq_len_src, tokens_src, surv
         _ptr(out["n_pages_used"], torch.int64, "n_pages_used"),
         _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
     _check("arrol_compact", rc)
+    return out
+
+
+def arrol_compact_static(kv_src, kv_dst, block_table_src, seq_len_src, tokens_src, survivor_idx, out, stream=None):
+    """arrol_compact without a workspace: the library's fixed scratch array is used and nothing is allocated
+    (every output tensor is the caller's: `out` as returned by arrol_compact)."""
+    n_src, ppr = block_table_src.shape
+    n_keep = survivor_idx.numel()
+    max_len = tokens_src.shape[1] if tokens_src is not None else 0
+    rc = lib().arrol_compact_static(
+        _ptr(kv_src, torch.bfloat16, "kv_src"), kv_layout_of(kv_src),
+        _ptr(kv_dst, torch.bfloat16, "kv_dst"), kv_layout_of(kv_dst),
+        _ptr(block_table_src, torch.int32, "block_table_src"), _ptr(seq_len_src, torch.int32, "seq_len_src"),
+        ppr, _ptr(tokens_src, torch.int32, "tokens_src"), max_len,
+        _ptr(survivor_idx, torch.int32, "survivor_idx"), n_src, n_keep,
+        _ptr(out["block_table_dst"], torch.int32, "block_table_dst"), _ptr(out["seq_len_dst"], torch.int32, "seq_len_dst"),
+        _ptr(out["tokens_dst"], torch.int32, "tokens_dst"), _ptr(out["src_of_dst"], torch.int32, "src_of_dst"),
+        _ptr(out["n_pages_used"], torch.int64, "n_pages_used"), _stream(stream))
+    _check("arrol_compact_static", rc)
     return out
 
 

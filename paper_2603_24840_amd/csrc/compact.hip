@@ -256,19 +256,33 @@ extern "C" size_t arrol_compact_workspace_bytes(int32_t n_keep) {
     return ((static_cast<size_t>(n_keep) + 1) * sizeof(int32_t) + 255) & ~static_cast<size_t>(255);
 }
 
-extern "C" int arrol_compact(const void* kv_src, arrol_kv_layout src, void* kv_dst, arrol_kv_layout dst,
-                             const int32_t* block_table_src, const int32_t* seq_len_src,
-                             int32_t max_pages_per_seq, const int32_t* tokens_src, int32_t max_len,
-                             const int32_t* survivor_idx, int32_t n_src, int32_t n_keep,
-                             int32_t* block_table_dst, int32_t* seq_len_dst, int32_t* tokens_dst,
-                             int32_t* src_of_dst, int64_t* n_pages_used,
-                             void* workspace, size_t workspace_bytes, void* stream) {
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    if (n_keep < 0 || n_src < 0 || !n_pages_used) return ARROL_EINVAL;
-    if (n_keep == 0) {
-        arrol_launch(compact_empty_kernel, dim3(1), dim3(1), 0, st, n_pages_used);
-        return arrol_launch_status();
-    }
+// ---- scratch of arrol_compact_static: one base offset per survivor plus the total, in device memory that
+// is part of the loaded code object (nothing is allocated at run time).  Every GPU the library runs on holds
+// its own copy at its own address; the address is looked up once per device and kept.
+static __device__ __align__(256) int32_t scratch[ARROL_COMPACT_STATIC_MAX_KEEP + 1];
+static std::atomic<int32_t*> g_scratch_ptr[64];
+
+static int32_t* static_scratch_of_current_device() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    int32_t* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    void* sym = nullptr;
+    if (hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)) != hipSuccess || !sym) return nullptr;
+    p = static_cast<int32_t*>(sym);
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+    return p;
+}
+
+namespace {
+
+// Argument checks and the two launches shared by arrol_compact and arrol_compact_static; `base` is the
+// int32 [n_keep + 1] scratch (caller's workspace or the library's static array), already validated.
+int compact_validate(const void* kv_src, const arrol_kv_layout& src, const void* kv_dst, const arrol_kv_layout& dst,
+                     const int32_t* block_table_src, const int32_t* seq_len_src, int32_t max_pages_per_seq,
+                     const int32_t* tokens_src, int32_t max_len, const int32_t* survivor_idx,
+                     const int32_t* block_table_dst, const int32_t* seq_len_dst, const int32_t* tokens_dst,
+                     const int32_t* src_of_dst) {
     if (!same_geometry(src, dst) || src.n_layers < 1 || src.page_tokens < 1 || src.n_kv_heads < 1 ||
         src.head_dim < 1 || src.n_pages < 0 || dst.n_pages < 0 || max_pages_per_seq < 1)
         return ARROL_EINVAL;
@@ -284,23 +298,81 @@ extern "C" int arrol_compact(const void* kv_src, arrol_kv_layout src, void* kv_d
     const char* b0 = static_cast<const char*>(kv_dst);
     const int64_t a_len = chunk_bytes * src.n_pages * src.n_layers * 2, b_len = chunk_bytes * dst.n_pages * dst.n_layers * 2;
     if (a0 < b0 + b_len && b0 < a0 + a_len) return ARROL_EINVAL;
-    if (!workspace || !arrol_aligned16(workspace) || workspace_bytes < arrol_compact_workspace_bytes(n_keep))
-        return ARROL_EWORKSPACE;
+    return ARROL_OK;
+}
+
+int compact_enqueue(const void* kv_src, const arrol_kv_layout& src, void* kv_dst, const arrol_kv_layout& dst,
+                    const int32_t* block_table_src, const int32_t* seq_len_src, int32_t max_pages_per_seq,
+                    const int32_t* tokens_src, int32_t max_len, const int32_t* survivor_idx, int32_t n_src,
+                    int32_t n_keep, int32_t* block_table_dst, int32_t* seq_len_dst, int32_t* tokens_dst,
+                    int32_t* src_of_dst, int64_t* n_pages_used, int32_t* base, hipStream_t st) {
+    const int64_t chunk_bytes = static_cast<int64_t>(src.page_tokens) * src.n_kv_heads * src.head_dim * 2;
+    const bool with_tokens = tokens_src != nullptr;
     const int64_t slots = static_cast<int64_t>(n_keep) * max_pages_per_seq;
     if (slots > INT32_MAX) return ARROL_EINVAL;  // page ids are int32
     const int64_t kv_blocks = slots * src.n_layers * 2;
     const int64_t blocks = kv_blocks + (with_tokens && max_len > 0 ? n_keep : 0);
     if (blocks > INT32_MAX) return ARROL_EINVAL;
-    int32_t* base = static_cast<int32_t*>(workspace);
     arrol_launch(compact_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, survivor_idx, seq_len_src, n_src,
-                       n_keep, src.page_tokens, max_pages_per_seq, base, block_table_dst, seq_len_dst, src_of_dst,
-                       n_pages_used);
+                 n_keep, src.page_tokens, max_pages_per_seq, base, block_table_dst, seq_len_dst, src_of_dst,
+                 n_pages_used);
     if (arrol_launch_failed()) return arrol_launch_status();
     arrol_launch(compact_copy_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kCopyThreads), 0, st,
-                       static_cast<const u32x4*>(kv_src), static_cast<u32x4*>(kv_dst), chunk_bytes / 16,
-                       src.n_pages, dst.n_pages, block_table_src, survivor_idx, base, n_src, n_keep,
-                       max_pages_per_seq, kv_blocks, tokens_src, tokens_dst, max_len);
+                 static_cast<const u32x4*>(kv_src), static_cast<u32x4*>(kv_dst), chunk_bytes / 16,
+                 src.n_pages, dst.n_pages, block_table_src, survivor_idx, base, n_src, n_keep,
+                 max_pages_per_seq, kv_blocks, tokens_src, tokens_dst, max_len);
     return arrol_launch_status();
+}
+
+}  // namespace
+
+extern "C" int arrol_compact(const void* kv_src, arrol_kv_layout src, void* kv_dst, arrol_kv_layout dst,
+                             const int32_t* block_table_src, const int32_t* seq_len_src,
+                             int32_t max_pages_per_seq, const int32_t* tokens_src, int32_t max_len,
+                             const int32_t* survivor_idx, int32_t n_src, int32_t n_keep,
+                             int32_t* block_table_dst, int32_t* seq_len_dst, int32_t* tokens_dst,
+                             int32_t* src_of_dst, int64_t* n_pages_used,
+                             void* workspace, size_t workspace_bytes, void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (n_keep < 0 || n_src < 0 || !n_pages_used) return ARROL_EINVAL;
+    if (n_keep == 0) {
+        arrol_launch(compact_empty_kernel, dim3(1), dim3(1), 0, st, n_pages_used);
+        return arrol_launch_status();
+    }
+    const int rc = compact_validate(kv_src, src, kv_dst, dst, block_table_src, seq_len_src, max_pages_per_seq,
+                                    tokens_src, max_len, survivor_idx, block_table_dst, seq_len_dst, tokens_dst,
+                                    src_of_dst);
+    if (rc != ARROL_OK) return rc;
+    if (!workspace || !arrol_aligned16(workspace) || workspace_bytes < arrol_compact_workspace_bytes(n_keep))
+        return ARROL_EWORKSPACE;
+    return compact_enqueue(kv_src, src, kv_dst, dst, block_table_src, seq_len_src, max_pages_per_seq, tokens_src,
+                           max_len, survivor_idx, n_src, n_keep, block_table_dst, seq_len_dst, tokens_dst,
+                           src_of_dst, n_pages_used, static_cast<int32_t*>(workspace), st);
+}
+
+extern "C" int arrol_compact_static(const void* kv_src, arrol_kv_layout src, void* kv_dst, arrol_kv_layout dst,
+                                    const int32_t* block_table_src, const int32_t* seq_len_src,
+                                    int32_t max_pages_per_seq, const int32_t* tokens_src, int32_t max_len,
+                                    const int32_t* survivor_idx, int32_t n_src, int32_t n_keep,
+                                    int32_t* block_table_dst, int32_t* seq_len_dst, int32_t* tokens_dst,
+                                    int32_t* src_of_dst, int64_t* n_pages_used, void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (n_keep < 0 || n_src < 0 || !n_pages_used) return ARROL_EINVAL;
+    if (n_keep > ARROL_COMPACT_STATIC_MAX_KEEP) return ARROL_EWORKSPACE;   // the fixed scratch holds no more
+    if (n_keep == 0) {
+        arrol_launch(compact_empty_kernel, dim3(1), dim3(1), 0, st, n_pages_used);
+        return arrol_launch_status();
+    }
+    const int rc = compact_validate(kv_src, src, kv_dst, dst, block_table_src, seq_len_src, max_pages_per_seq,
+                                    tokens_src, max_len, survivor_idx, block_table_dst, seq_len_dst, tokens_dst,
+                                    src_of_dst);
+    if (rc != ARROL_OK) return rc;
+    int32_t* base = static_scratch_of_current_device();
+    if (!base) return ARROL_EHIP;
+    // base[0 .. n_keep] is rewritten in full by the plan kernel, so nothing has to be cleared between calls
+    return compact_enqueue(kv_src, src, kv_dst, dst, block_table_src, seq_len_src, max_pages_per_seq, tokens_src,
+                           max_len, survivor_idx, n_src, n_keep, block_table_dst, seq_len_dst, tokens_dst,
+                           src_of_dst, n_pages_used, base, st);
 }
 
 extern "C" size_t arrol_compact_inplace_workspace_bytes(int64_t n_pages) {

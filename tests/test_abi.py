@@ -29,7 +29,7 @@ def test_header_declares_the_five_stage_calls():
     for fn in ["arrol_score", "arrol_select", "arrol_compact", "arrol_logprob", "arrol_weighted_vote",
                "arrol_compact_workspace_bytes", "arrol_logprob_workspace_bytes", "arrol_version",
                "arrol_error_string", "arrol_set_tuning", "arrol_histogram", "arrol_calibrate",
-               "arrol_prune_bernoulli", "arrol_compact_inplace", "arrol_compact_inplace_workspace_bytes",
+               "arrol_prune_bernoulli", "arrol_compact_static", "arrol_compact_inplace", "arrol_compact_inplace_workspace_bytes",
                "arrol_score_mlp", "arrol_score_grad", "arrol_score_grad_workspace_bytes", "arrol_adamw_step", "arrol_score_mlp_grad",
                "arrol_score_mlp_grad_workspace_bytes", "arrol_token_confidence",
                "arrol_token_confidence_workspace_bytes", "arrol_trace_confidence",
@@ -100,6 +100,12 @@ def test_bad_arguments_are_rejected_on_the_host(pkg):
     assert L.arrol_compact(fake, lay, fake, lay, *args, fake, 1 << 20, None) == -1      # overlapping pools
     assert L.arrol_compact(fake, lay, far, lay, *args, None, 0, None) == -2
     assert L.arrol_compact(fake, lay, far, lay, *args, fake, 4, None) == -2
+    # the variant without a workspace: same checks, and more survivors than its fixed scratch holds
+    sargs = (fake, fake, 4, None, 0, fake, 32, 16, fake, fake, None, fake, fake)
+    assert L.arrol_compact_static(fake, lay, far, other, *sargs, None) == -1
+    assert L.arrol_compact_static(fake, lay, fake, lay, *sargs, None) == -1
+    big = (fake, fake, 4, None, 0, fake, 1 << 20, 16384, fake, fake, None, fake, fake)
+    assert L.arrol_compact_static(fake, lay, far, lay, *big, None) == -2
     assert L.arrol_set_tuning(b"no_such_knob", 1) == -1
     # MLP head: bad d, m < 1, null weights
     assert L.arrol_score_mlp(fake, 16, None, fake, None, fake, 0.0, 4, 12, 8, None, fake, None) == -1
