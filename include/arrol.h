@@ -190,12 +190,16 @@ int arrol_compact_inplace(void* kv, arrol_kv_layout layout, const int32_t* block
  * logprob_out fp32 [T];  lse_out NULL or fp32 [T] (the logsumexp).
  * bf16 products accumulated in fp32 on the matrix cores; the [T, V] logits are never
  * written to memory.  T == 0 is a no-op.
- * workspace: arrol_logprob_workspace_bytes(T, V, d) bytes, 16-byte aligned.
+ * n_splits  number of ranges the vocabulary is cut into (each workgroup walks one range for its block of
+ *           tokens; the per-range partials are merged by a second small kernel).  0 lets the library
+ *           choose from T and V; a positive value is used as given, capped at the number of 256-row
+ *           vocabulary tiles.  The result does not depend on it beyond fp32 rounding of the merge.
+ * workspace: arrol_logprob_workspace_bytes(T, V, d, n_splits) bytes for the SAME n_splits, 16-byte aligned.
  */
-size_t arrol_logprob_workspace_bytes(int64_t T, int32_t V, int32_t d);
+size_t arrol_logprob_workspace_bytes(int64_t T, int32_t V, int32_t d, int32_t n_splits);
 int arrol_logprob(const void* hidden, const void* lm_head, const int32_t* targets,
                   int64_t T, int32_t V, int32_t d, float* logprob_out, float* lse_out,
-                  void* workspace, size_t workspace_bytes, void* stream);
+                  int32_t n_splits, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Stage 5 -- rank-weighted vote (Sec. 4.4: candidates are sorted by head score and their
@@ -375,13 +379,6 @@ int arrol_score_mlp_grad(const void* hidden, int64_t row_stride_elems, const int
 int arrol_adamw_step(float* param, const float* grad, float* m, float* v, int64_t n, int32_t step,
                      float lr, float beta1, float beta2, float eps, float weight_decay,
                      void* param_bf16, void* stream);
-
-/*
- * Benchmarking knob, not a stage of the method.  key "logprob_splits": number of vocabulary
- * splits arrol_logprob uses (0 = built-in heuristic).  Process-wide, not thread-safe; the
- * workspace size must be queried again after changing it.  Unknown key: ARROL_EINVAL.
- */
-int arrol_set_tuning(const char* key, int value);
 
 #ifdef __cplusplus
 }

@@ -5,6 +5,7 @@ for device memory and streams.  There is no CPU fallback: if the library is miss
 tensor is not on the GPU the call raises.
 """
 import ctypes
+import functools
 import os
 
 import torch
@@ -42,7 +43,6 @@ _vp, _i32, _i64, _f32, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ct
 _SIGNATURES = {
     "arrol_version": (ctypes.c_int, []),
     "arrol_error_string": (ctypes.c_char_p, [ctypes.c_int]),
-    "arrol_set_tuning": (ctypes.c_int, [ctypes.c_char_p, ctypes.c_int]),
     "arrol_score": (ctypes.c_int, [_vp, _i64, _vp, _vp, _f32, _i32, _i32, _vp, _vp, _vp]),
     "arrol_score_mlp": (ctypes.c_int, [_vp, _i64, _vp, _vp, _vp, _vp, _f32, _i32, _i32, _i32, _vp, _vp, _vp]),
     "arrol_score_grad_workspace_bytes": (_sz, [_i32, _i32]),
@@ -60,8 +60,8 @@ _SIGNATURES = {
     "arrol_compact_inplace_workspace_bytes": (_sz, [_i64]),
     "arrol_compact_inplace": (ctypes.c_int, [_vp, KVLayout, _vp, _vp, _i32, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp,
                                              _vp, _sz, _vp]),
-    "arrol_logprob_workspace_bytes": (_sz, [_i64, _i32, _i32]),
-    "arrol_logprob": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
+    "arrol_logprob_workspace_bytes": (_sz, [_i64, _i32, _i32, _i32]),
+    "arrol_logprob": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i32, _i32, _vp, _vp, _i32, _vp, _sz, _vp]),
     "arrol_token_confidence_workspace_bytes": (_sz, [_i32, _i32]),
     "arrol_token_confidence": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i32, _i32, _vp, _vp, _sz, _vp]),
     "arrol_trace_confidence_workspace_bytes": (_sz, [_i64, _i32]),
@@ -100,12 +100,6 @@ def error_string(code):
     return lib().arrol_error_string(code).decode()
 
 
-def set_tuning(key, value):
-    rc = lib().arrol_set_tuning(key.encode(), int(value))
-    if rc != OK:
-        raise ArrolError("arrol_set_tuning", rc)
-
-
 def _ptr(t, dtype=None, name="tensor"):
     if t is None:
         return None
@@ -128,6 +122,21 @@ def _check(fn, rc):
         raise ArrolError(fn, rc)
 
 
+def _on_stream(fn):
+    """Runs the wrapped call with `stream` (when given) as torch's current stream, so that every tensor the
+    binding creates itself - outputs and temporary workspaces - belongs to the stream the kernels are
+    enqueued on: the caching allocator then cannot hand a dropped temporary to other work while a kernel
+    of that stream still uses it."""
+    @functools.wraps(fn)
+    def wrapper(*args, stream=None, **kwargs):
+        if stream is None:
+            return fn(*args, stream=None, **kwargs)
+        with torch.cuda.stream(stream):
+            return fn(*args, stream=stream, **kwargs)
+    return wrapper
+
+
+@_on_stream
 def arrol_score(hidden, w, bias=0.0, row_index=None, out_score=None, out_prob=None, want_score=True,
                 stream=None):
     """hidden bf16 [R, d] (rows may be strided), w fp32 [d] -> (score fp32 [n], prob fp32 [n])."""
@@ -151,6 +160,7 @@ def arrol_score(hidden, w, bias=0.0, row_index=None, out_score=None, out_prob=No
     return out_score, out_prob
 
 
+@_on_stream
 def arrol_score_mlp(hidden, w1, b1, w2, b2=0.0, row_index=None, stream=None):
     """hidden bf16 [R, d], w1 bf16 [m, d], b1 fp32 [m] or None, w2 fp32 [m] -> (score, prob) fp32 [n]."""
     if hidden.dim() != 2 or hidden.dtype != torch.bfloat16 or not hidden.is_cuda or hidden.stride(1) != 1:
@@ -172,6 +182,7 @@ def arrol_score_mlp(hidden, w1, b1, w2, b2=0.0, row_index=None, stream=None):
     return score, prob
 
 
+@_on_stream
 def arrol_score_grad(hidden, w, bias, labels, row_index=None, workspace=None, stream=None):
     """Cross-entropy loss of the linear head and its gradient: hidden bf16 [R, d], w fp32 [d], labels fp32 [n]
     -> (loss fp32 [1], grad_w fp32 [d], grad_bias fp32 [1])."""
@@ -197,6 +208,7 @@ def arrol_score_grad(hidden, w, bias, labels, row_index=None, workspace=None, st
     return loss, grad_w, grad_b
 
 
+@_on_stream
 def arrol_score_mlp_grad(hidden, w1, b1, w2, b2, labels, row_index=None, workspace=None, stream=None):
     """Cross-entropy loss of the MLP head and its gradients: -> dict(loss [1], grad_w1 [m, d], grad_b1 [m],
     grad_w2 [m], grad_b2 [1]), all fp32."""
@@ -226,6 +238,7 @@ def arrol_score_mlp_grad(hidden, w1, b1, w2, b2, labels, row_index=None, workspa
     return out
 
 
+@_on_stream
 def arrol_adamw_step(param, grad, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0,
                      param_bf16=None, stream=None):
     """In-place AdamW update of fp32 param / m / v (all [n]); param_bf16 (optional, bf16 [n]) gets a rounded copy."""
@@ -240,6 +253,7 @@ def arrol_adamw_step(param, grad, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e
     return param
 
 
+@_on_stream
 def arrol_select(prob, n_groups, G, K, rho=0.5, out_keep=None, out_survivors=None, stream=None):
     """prob fp32 [n_groups*G] -> (keep_mask uint8 [n_groups*G], survivor_idx int32 [n_groups*K])."""
     dev = prob.device
@@ -268,6 +282,7 @@ def arrol_compact_workspace_bytes(n_keep):
     return lib().arrol_compact_workspace_bytes(n_keep)
 
 
+@_on_stream
 def arrol_compact(kv_src, kv_dst, block_table_src, seq_len_src, tokens_src, survivor_idx,
                   out=None, workspace=None, stream=None):
     """Gathers survivors into kv_dst (written in place).  Returns a dict with block_table_dst,
@@ -301,6 +316,7 @@ def arrol_compact(kv_src, kv_dst, block_table_src, seq_len_src, tokens_src, surv
     return out
 
 
+@_on_stream
 def arrol_compact_static(kv_src, kv_dst, block_table_src, seq_len_src, tokens_src, survivor_idx, out, stream=None):
     """arrol_compact without a workspace: the library's fixed scratch array is used and nothing is allocated
     (every output tensor is the caller's: `out` as returned by arrol_compact)."""
@@ -320,6 +336,7 @@ def arrol_compact_static(kv_src, kv_dst, block_table_src, seq_len_src, tokens_sr
     return out
 
 
+@_on_stream
 def arrol_compact_inplace(kv, block_table_src, seq_len_src, survivor_idx, workspace=None, stream=None):
     """Moves the survivors' pages into the dense prefix of the SAME pool (kv is modified in place).
     Returns dict(block_table_dst, seq_len_dst, src_of_dst, n_pages_used, n_moved)."""
@@ -345,13 +362,15 @@ def arrol_compact_inplace(kv, block_table_src, seq_len_src, survivor_idx, worksp
     return out
 
 
-def arrol_logprob_workspace_bytes(T, V, d):
-    return lib().arrol_logprob_workspace_bytes(T, V, d)
+def arrol_logprob_workspace_bytes(T, V, d, n_splits=0):
+    return lib().arrol_logprob_workspace_bytes(T, V, d, n_splits)
 
 
+@_on_stream
 def arrol_logprob(hidden, lm_head, targets, out_logprob=None, out_lse=None, want_lse=False,
-                  workspace=None, stream=None):
-    """hidden bf16 [T, d], lm_head bf16 [V, d], targets int32 [T] -> logprob fp32 [T] (and lse)."""
+                  n_splits=0, workspace=None, stream=None):
+    """hidden bf16 [T, d], lm_head bf16 [V, d], targets int32 [T] -> logprob fp32 [T] (and lse).
+    n_splits = number of vocabulary ranges (0: the library chooses)."""
     T, d = hidden.shape
     V = lm_head.shape[0]
     if lm_head.shape[1] != d:
@@ -361,17 +380,18 @@ def arrol_logprob(hidden, lm_head, targets, out_logprob=None, out_lse=None, want
         out_logprob = torch.empty(T, dtype=torch.float32, device=dev)
     if out_lse is None and want_lse:
         out_lse = torch.empty(T, dtype=torch.float32, device=dev)
-    need = arrol_logprob_workspace_bytes(T, V, d)
+    need = arrol_logprob_workspace_bytes(T, V, d, n_splits)
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
     rc = lib().arrol_logprob(_ptr(hidden, torch.bfloat16, "hidden"), _ptr(lm_head, torch.bfloat16, "lm_head"),
                              _ptr(targets, torch.int32, "targets"), T, V, d,
                              _ptr(out_logprob, torch.float32, "logprob_out"), _ptr(out_lse, torch.float32, "lse_out"),
-                             _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
+                             int(n_splits), _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
     _check("arrol_logprob", rc)
     return (out_logprob, out_lse) if (want_lse or out_lse is not None) else out_logprob
 
 
+@_on_stream
 def arrol_token_confidence(hidden, lm_head, lse, workspace=None, stream=None):
     """hidden bf16 [T, d], lm_head bf16 [V, d], lse fp32 [T] (from arrol_logprob) -> token confidence fp32 [T]."""
     if hidden.dim() != 2 or lm_head.dim() != 2 or hidden.shape[1] != lm_head.shape[1]:
@@ -391,6 +411,7 @@ def arrol_token_confidence(hidden, lm_head, lse, workspace=None, stream=None):
     return conf
 
 
+@_on_stream
 def arrol_trace_confidence(conf, cu_seqlens, window, bottom_percent=10, workspace=None, stream=None):
     """conf fp32 [T], cu_seqlens int64 [n+1] -> (trace mean, min window mean, bottom-share window mean) fp64 [n]."""
     T = conf.numel()
@@ -409,6 +430,7 @@ def arrol_trace_confidence(conf, cu_seqlens, window, bottom_percent=10, workspac
     return tuple(outs)
 
 
+@_on_stream
 def arrol_grpo_advantage(reward, group_offsets, ddof=0, eps=0.0, stream=None):
     """reward fp32 [N], group_offsets int64 [n_groups+1] -> (advantage fp32 [N], seq_weight fp32 [N])."""
     N = reward.numel()
@@ -421,6 +443,7 @@ def arrol_grpo_advantage(reward, group_offsets, ddof=0, eps=0.0, stream=None):
     return adv, wgt
 
 
+@_on_stream
 def arrol_grpo_objective(logp, logp_ref, cu_seqlens, advantage, seq_weight, eps_low=0.2, eps_high=0.2, beta=0.0,
                          want_grad=True, workspace=None, stream=None):
     """-> (J fp64 [1], dJ/dlogp fp32 [T] or None, n_clipped int64 [1])."""
@@ -444,6 +467,7 @@ def arrol_grpo_objective(logp, logp_ref, cu_seqlens, advantage, seq_weight, eps_
     return J, grad, n_clip
 
 
+@_on_stream
 def arrol_weighted_vote(prob, answer_id, n_questions, C, n_answers, want_tally=False, out_winner=None, stream=None):
     """prob fp32 [Q*C], answer_id int32 [Q*C] -> winner int32 [Q] (and tally int64 [Q, A])."""
     dev = prob.device
@@ -460,6 +484,7 @@ def arrol_weighted_vote(prob, answer_id, n_questions, C, n_answers, want_tally=F
     return (winner, tally) if want_tally else winner
 
 
+@_on_stream
 def arrol_histogram(s_norm, label, B, stream=None):
     """s_norm fp32 [M] in [0,1], label uint8 [M] -> (c_pos, c_neg) int64 [B]."""
     dev = s_norm.device
@@ -471,6 +496,7 @@ def arrol_histogram(s_norm, label, B, stream=None):
     return c_pos, c_neg
 
 
+@_on_stream
 def arrol_calibrate(c_pos, c_neg, policy, stream=None):
     """int64 histograms [B] + Policy -> (q_lut fp32 [B], p_lut fp32 [B], delta fp64 device scalar)."""
     B = c_pos.numel()
@@ -484,6 +510,7 @@ def arrol_calibrate(c_pos, c_neg, policy, stream=None):
     return q_lut, p_lut, delta
 
 
+@_on_stream
 def arrol_prune_bernoulli(s_norm, uniforms, p_lut, want_p=False, stream=None):
     """s_norm, uniforms fp32 [N], p_lut fp32 [B] -> dict(keep_mask, survivor_idx (padded with -1),
     n_survivors (device int32), p (optional))."""

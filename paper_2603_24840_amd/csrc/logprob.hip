@@ -574,16 +574,13 @@ using MainTile = Tile<256, 256, 64, 2, 4>;
 using FastTile = RingTile<256, 256, 2, 4>;
 static_assert(MainTile::BM == FastTile::BM && MainTile::BN == FastTile::BN, "one plan serves both kernels");
 
-int g_force_splits = 0;  // 0 = heuristic
-int g_force_general = 0; // 1 = use the general kernel even when d % 64 == 0
-
 struct Plan { int n_tb, n_vt, n_sp; };
 
-Plan make_plan(int64_t T, int V) {
+Plan make_plan(int64_t T, int V, int n_splits) {
     Plan p;
     p.n_tb = static_cast<int>((T + MainTile::BN - 1) / MainTile::BN);
     p.n_vt = (V + MainTile::BM - 1) / MainTile::BM;
-    int sp = g_force_splits;
+    int sp = n_splits;
     if (sp <= 0) {
         // enough workgroups to fill 256 CUs several times over; 8 splits make the
         // 32 workgroups resident on an XCD a 4-token-block x 8-split patch
@@ -598,30 +595,23 @@ Plan make_plan(int64_t T, int V) {
 
 }  // namespace
 
-extern "C" int arrol_set_tuning(const char* key, int value) {
-    if (!key) return ARROL_EINVAL;
-    if (!__builtin_strcmp(key, "logprob_splits")) { g_force_splits = value; return ARROL_OK; }
-    if (!__builtin_strcmp(key, "logprob_general_kernel")) { g_force_general = value; return ARROL_OK; }
-    return ARROL_EINVAL;
-}
-
-extern "C" size_t arrol_logprob_workspace_bytes(int64_t T, int32_t V, int32_t d) {
+extern "C" size_t arrol_logprob_workspace_bytes(int64_t T, int32_t V, int32_t d, int32_t n_splits) {
     (void)d;
-    if (T <= 0 || V < 1) return 0;
-    const Plan p = make_plan(T, V);
+    if (T <= 0 || V < 1 || n_splits < 0) return 0;
+    const Plan p = make_plan(T, V, n_splits);
     return (static_cast<size_t>(p.n_sp) * 3 * static_cast<size_t>(T) * sizeof(float) + 255) & ~static_cast<size_t>(255);
 }
 
 extern "C" int arrol_logprob(const void* hidden, const void* lm_head, const int32_t* targets,
                              int64_t T, int32_t V, int32_t d, float* logprob_out, float* lse_out,
-                             void* workspace, size_t workspace_bytes, void* stream) {
-    if (T < 0 || V < 1 || d < 8 || (d & 7)) return ARROL_EINVAL;
+                             int32_t n_splits, void* workspace, size_t workspace_bytes, void* stream) {
+    if (T < 0 || V < 1 || d < 8 || (d & 7) || n_splits < 0) return ARROL_EINVAL;
     if (T == 0) return ARROL_OK;
     if (!hidden || !lm_head || !targets || !logprob_out || !arrol_aligned16(hidden) || !arrol_aligned16(lm_head))
         return ARROL_EINVAL;
-    const Plan p = make_plan(T, V);
+    const Plan p = make_plan(T, V, n_splits);
     if (static_cast<int64_t>(p.n_tb) + kXcds > INT32_MAX / p.n_sp) return ARROL_EINVAL;
-    if (!workspace || !arrol_aligned16(workspace) || workspace_bytes < arrol_logprob_workspace_bytes(T, V, d))
+    if (!workspace || !arrol_aligned16(workspace) || workspace_bytes < arrol_logprob_workspace_bytes(T, V, d, n_splits))
         return ARROL_EWORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     static arrol_device_flags general_ok, fast_ok;
@@ -636,7 +626,7 @@ extern "C" int arrol_logprob(const void* hidden, const void* lm_head, const int3
     a.T = T; a.V = V; a.d = d;
     a.n_tb = p.n_tb; a.n_sp = p.n_sp; a.n_vt = p.n_vt;
     const int tb_pad = (p.n_tb + kXcds - 1) / kXcds * kXcds;
-    if (d % 64 == 0 && !g_force_general)
+    if (d % 64 == 0)
         arrol_launch(logprob_ring_kernel<FastTile>, dim3(tb_pad * p.n_sp), dim3(FastTile::NT), FastTile::LDS_BYTES, st, a);
     else
         arrol_launch(logprob_kernel<MainTile>, dim3(tb_pad * p.n_sp), dim3(MainTile::NT), MainTile::LDS_BYTES, st, a);

@@ -9,6 +9,7 @@ oracle's scoring is involved.
 """
 from dataclasses import dataclass, replace
 
+import numpy as np
 import torch
 
 BASE_SEED = 260324840
@@ -152,7 +153,49 @@ def logprob_inputs(cfg, device, T=None, vocab=None):
     lm_head = randn_bf16((V, cfg.d), g, device, std=cfg.d ** -0.5)
     hidden = randn_bf16((total, cfg.d), g, device)
     targets = torch.randint(0, V, (total,), generator=g, device=device, dtype=torch.int32)
+    for row, value in edge_target_rows(total, V):
+        targets[row] = value
     return hidden, lm_head, targets, cu
+
+
+VOCAB_TILE = 256    # edge cases are planted on multiples of this (the vocabulary is processed in 256-row tiles)
+
+
+def edge_target_rows(T, V):
+    """(row, target) pairs written over the uniform targets so that every batch, whatever its size, holds the
+    edge targets a check must see: 0, V-1, both sides of the first vocabulary-tile edge and of the last one."""
+    last_edge = (V - 1) // VOCAB_TILE * VOCAB_TILE
+    values = [0, V - 1, min(VOCAB_TILE - 1, V - 1), min(VOCAB_TILE, V - 1), max(last_edge - 1, 0), last_edge]
+    if T < 8 * len(values):
+        return []
+    return [((k + 1) * T // (len(values) + 2), v) for k, v in enumerate(values)]
+
+
+def logprob_check_rows(T, n, V, cu=None, seed=7):
+    """Sorted row sample of size about n for comparing log-probs against the oracle: a seeded random draw
+    plus the rows that must always be looked at - row 0, row T-1, both sides of the first token-tile edge,
+    the first and last row of the first and last survivor (from cu_seqlens), and the rows that carry the
+    planted edge targets."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed)
+    rows = set(torch.randperm(T, generator=g)[:max(0, n)].tolist())
+    rows.update(r for r in (0, 1, T - 2, T - 1, VOCAB_TILE - 1, VOCAB_TILE) if 0 <= r < T)
+    if cu is not None and len(cu) >= 2:
+        c = [int(x) for x in cu]
+        rows.update(r for r in (c[0], c[1] - 1, c[-2], c[-1] - 1) if 0 <= r < T)
+    rows.update(r for r, _ in edge_target_rows(T, V))
+    return torch.tensor(sorted(rows), dtype=torch.int64)
+
+
+def bits(t):
+    """bf16 torch tensor (any device) -> uint16 numpy array of its bit patterns (what the oracle takes)."""
+    assert t.dtype == torch.bfloat16
+    return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
+def npy(t):
+    """torch tensor (any device) -> numpy array on the host."""
+    return t.detach().cpu().numpy()
 
 
 def vote_inputs(cfg, device):

@@ -2,15 +2,7 @@
 import numpy as np
 import torch
 
-
-def bits(t):
-    """bf16 torch tensor (any device) -> uint16 numpy array of its bit patterns."""
-    assert t.dtype == torch.bfloat16
-    return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
-
-
-def npy(t):
-    return t.detach().cpu().numpy()
+from paper_2603_24840_amd.workloads import bits, npy  # noqa: F401  (host views shared with bench.py and smoke())
 
 
 def f32_to_bf16_bits(x):

@@ -28,7 +28,7 @@ def test_header_declares_the_five_stage_calls():
     names = declared_functions()
     for fn in ["arrol_score", "arrol_select", "arrol_compact", "arrol_logprob", "arrol_weighted_vote",
                "arrol_compact_workspace_bytes", "arrol_logprob_workspace_bytes", "arrol_version",
-               "arrol_error_string", "arrol_set_tuning", "arrol_histogram", "arrol_calibrate",
+               "arrol_error_string", "arrol_histogram", "arrol_calibrate",
                "arrol_prune_bernoulli", "arrol_compact_static", "arrol_compact_inplace", "arrol_compact_inplace_workspace_bytes",
                "arrol_score_mlp", "arrol_score_grad", "arrol_score_grad_workspace_bytes", "arrol_adamw_step", "arrol_score_mlp_grad",
                "arrol_score_mlp_grad_workspace_bytes", "arrol_token_confidence",
@@ -81,11 +81,16 @@ def test_bad_arguments_are_rejected_on_the_host(pkg):
     assert L.arrol_score(ctypes.c_void_p(0x1004), 16, None, fake, 0.0, 4, 16, None, fake, None) == -1
     assert L.arrol_score(None, 16, None, None, 0.0, 0, 16, None, None, None) == 0
     # logprob: bad d, missing workspace
-    assert L.arrol_logprob(fake, fake, fake, 10, 100, 12, fake, None, fake, 1 << 20, None) == -1
-    assert L.arrol_logprob(fake, fake, fake, 10, 0, 16, fake, None, fake, 1 << 20, None) == -1
-    assert L.arrol_logprob(fake, fake, fake, 10, 100, 16, fake, None, None, 0, None) == -2
-    assert L.arrol_logprob(fake, fake, fake, 10, 100, 16, fake, None, fake, 8, None) == -2
-    assert L.arrol_logprob(None, None, None, 0, 100, 16, None, None, None, 0, None) == 0
+    assert L.arrol_logprob(fake, fake, fake, 10, 100, 12, fake, None, 0, fake, 1 << 20, None) == -1
+    assert L.arrol_logprob(fake, fake, fake, 10, 0, 16, fake, None, 0, fake, 1 << 20, None) == -1
+    assert L.arrol_logprob(fake, fake, fake, 10, 100, 16, fake, None, -1, fake, 1 << 20, None) == -1     # n_splits < 0
+    assert L.arrol_logprob(fake, fake, fake, 10, 100, 16, fake, None, 0, None, 0, None) == -2
+    assert L.arrol_logprob(fake, fake, fake, 10, 100, 16, fake, None, 0, fake, 8, None) == -2
+    # a workspace sized for 2 splits is too small for 8 (600 rows x 4500 vocabulary entries = 18 tiles)
+    two = L.arrol_logprob_workspace_bytes(600, 4500, 64, 2)
+    assert L.arrol_logprob_workspace_bytes(600, 4500, 64, 8) > two >= 600 * 2 * 12
+    assert L.arrol_logprob(fake, fake, fake, 600, 4500, 64, fake, None, 8, fake, two, None) == -2
+    assert L.arrol_logprob(None, None, None, 0, 100, 16, None, None, 0, None, 0, None) == 0
     # vote: C > 64, no answers
     assert L.arrol_weighted_vote(fake, fake, 3, 65, 4, fake, None, None) == -1
     assert L.arrol_weighted_vote(fake, fake, 3, 8, 0, fake, None, None) == -1
@@ -106,7 +111,6 @@ def test_bad_arguments_are_rejected_on_the_host(pkg):
     assert L.arrol_compact_static(fake, lay, fake, lay, *sargs, None) == -1
     big = (fake, fake, 4, None, 0, fake, 1 << 20, 16384, fake, fake, None, fake, fake)
     assert L.arrol_compact_static(fake, lay, far, lay, *big, None) == -2
-    assert L.arrol_set_tuning(b"no_such_knob", 1) == -1
     # MLP head: bad d, m < 1, null weights
     assert L.arrol_score_mlp(fake, 16, None, fake, None, fake, 0.0, 4, 12, 8, None, fake, None) == -1
     assert L.arrol_score_mlp(fake, 16, None, fake, None, fake, 0.0, 4, 16, 0, None, fake, None) == -1

@@ -1,6 +1,8 @@
-"""Parity at the benchmark's full size (LLaMA-3.2-1B-shaped batch, same launch configuration
-bench.py times) on sampled outputs the oracle computes one by one, plus reduced-batch cases
-with the other configurations' geometry (d, vocab size, head_dim, group size)."""
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times: every configuration
+(LLaMA-3.2-1B-, Qwen3-1.7B-, LLaMA-3.2-3B- and Qwen3-8B-shaped batches) on sampled outputs the oracle
+computes one by one - log-probs on a seeded row sample that always holds the edge rows, compaction byte
+for byte on the first, a middle and the last KV layer plus a gather property on every layer - and
+reduced-batch cases with the same geometries (ragged pools with spare pages)."""
 import numpy as np
 import pytest
 import torch
@@ -29,18 +31,25 @@ def say(msg):
     print("[case] " + msg, flush=True)
 
 
-def sample_rows(T, n, V, targets, seed=7):
-    """Seeded row sample that always holds the first / last rows and rows whose target sits on a
-    vocabulary-tile edge or at the ends of the vocabulary."""
-    g = torch.Generator(device="cpu"); g.manual_seed(seed)
-    rows = set(torch.randperm(T, generator=g)[:n].tolist())
-    rows.update([0, 1, T - 1, T - 2, min(T - 1, 255), min(T - 1, 256)])
+def sample_rows(T, n, V, targets, seed=7, cu=None):
+    """Seeded row sample that always holds the first / last rows, the first and last row of the first and last
+    survivor, and rows whose target sits on a vocabulary-tile edge or at the ends of the vocabulary (the
+    input generator plants such targets; any other row that happens to carry one is added too)."""
+    from paper_2603_24840_amd.workloads import logprob_check_rows
+    rows = set(logprob_check_rows(T, n, V, cu, seed).tolist())
     t = npy(targets)
-    for want in (0, V - 1, 255, 256, (V // 256) * 256 - 1, (V // 256) * 256 % V):
+    last_edge = (V - 1) // 256 * 256
+    for want in (0, V - 1, 255, 256, last_edge - 1, last_edge):
         hit = np.flatnonzero(t == want)
         if hit.size:
             rows.add(int(hit[0]))
     return torch.tensor(sorted(rows), dtype=torch.int64)
+
+
+def free():
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()
 
 
 def test_llama1b_prune_path_full_size(A, W):
@@ -106,13 +115,102 @@ def test_llama1b_logprob_full_size_sampled_rows(A, W):
     assert 256 * cfg.n_keep <= T <= 2048 * cfg.n_keep and lm_head.shape == (128256, 2048)
     lp, lse = A.arrol_logprob(hidden, lm_head, targets, want_lse=True)
     torch.cuda.synchronize()
-    rows = sample_rows(T, 150, cfg.vocab, targets)
+    rows = sample_rows(T, 150, cfg.vocab, targets, cu=cu)
     lp_o, lse_o = O.logprob(bits(hidden[rows.to(DEV)]), bits(lm_head), npy(targets)[rows.numpy()])
     assert np.max(np.abs(npy(lp)[rows.numpy()] - lp_o)) < 1e-4      # the bar is 2e-3; 1e-4 is what fp32 accumulation allows here
     assert np.max(np.abs(npy(lse)[rows.numpy()] - lse_o)) < 1e-4
     # whole output: finite, negative, and distributed as logits ~ N(0,1) imply (lse ~ log V + 1/2)
     assert bool(torch.isfinite(lp).all()) and float(lp.max()) <= 0.0
     assert abs(float(lse.mean()) - (np.log(cfg.vocab) + 0.5)) < 0.05
+
+
+BIG = ["qwen1p7b", "llama3b", "qwen8b"]
+
+
+@pytest.mark.parametrize("name", BIG)
+def test_prune_and_compact_full_size(A, W, name):
+    """score -> select -> compact on the whole batch and the whole KV pool (120-155 GB source, 60-77 GB
+    destination): the library's chain against the oracle's chain from the same seeded inputs."""
+    cfg = W.CONFIGS[name]
+    say("%s score/select/vote full batch, then compact of the full pool" % name)
+    free()
+    hidden, w, b = W.score_inputs(cfg, DEV)
+    s, q = A.arrol_score(hidden, w, b)
+    keep, surv = A.arrol_select(q, cfg.n_prompts, cfg.G, cfg.K, cfg.rho)
+    torch.cuda.synchronize()
+    so, qo = O.score(bits(hidden), npy(w), b)
+    assert np.max(np.abs(npy(q) - qo)) < 1e-3 and np.max(np.abs(npy(s) - so)) < 1e-3
+    q32 = qo.astype(np.float32)
+    keep_o, surv_o = oracle_survivors(O, q32, cfg)
+    keep2, surv2 = A.arrol_select(to_dev(q32, DEV), cfg.n_prompts, cfg.G, cfg.K, cfg.rho)
+    torch.cuda.synchronize()
+    assert np.array_equal(npy(keep2), keep_o) and np.array_equal(npy(surv2), surv_o)     # stage parity
+    assert np.array_equal(npy(keep), keep_o) and np.array_equal(npy(surv), surv_o)       # chain parity
+    if cfg.vote_q * cfg.vote_c <= cfg.n_rollouts:       # the benchmark votes on the batch's own probabilities
+        _, ans = W.vote_inputs(cfg, DEV)
+        n = cfg.vote_q * cfg.vote_c
+        win, tally = A.arrol_weighted_vote(q[:n].contiguous(), ans, cfg.vote_q, cfg.vote_c, cfg.vote_a, want_tally=True)
+        torch.cuda.synchronize()
+        win_o, tally_o = O.weighted_vote(q32[:n], npy(ans), cfg.vote_q, cfg.vote_c, cfg.vote_a)
+        assert np.array_equal(npy(win), win_o) and np.array_equal(npy(tally), tally_o)
+    del hidden
+    say("%s pool: %d pages x %d layers" % (name, cfg.n_rollouts * cfg.pages_per_rollout, cfg.n_layers))
+    kv, bt, sl, tok = W.compact_inputs(cfg, DEV)
+    n_dst = cfg.n_keep * cfg.pages_per_rollout
+    dst = torch.empty((cfg.n_layers, 2, n_dst) + tuple(kv.shape[3:]), dtype=torch.bfloat16, device=DEV)
+    for layer in range(cfg.n_layers):                   # NaN pattern: a page the call skips stays visible
+        dst[layer].view(torch.int16).fill_(0x7FC1)
+    out = A.arrol_compact(kv, dst, bt, sl, tok, surv)
+    torch.cuda.synchronize()
+    say("%s compact done; oracle on layers 0, %d, %d" % (name, cfg.n_layers // 2, cfg.n_layers - 1))
+    bt_h, sl_h, tok_h = npy(bt), npy(sl), npy(tok)
+    ref = None
+    for layer in (0, cfg.n_layers // 2, cfg.n_layers - 1):
+        ref = O.compact(bits(kv[layer:layer + 1]), bt_h, sl_h, tok_h, surv_o, n_dst, fill=0x7FC1)
+        assert np.array_equal(bits(dst[layer:layer + 1]), ref["kv_dst"]), layer
+        say("%s layer %d bit-exact" % (name, layer))
+    assert np.array_equal(npy(out["block_table_dst"]), ref["block_table_dst"])
+    assert np.array_equal(npy(out["tokens_dst"]), ref["tokens_dst"])
+    assert np.array_equal(npy(out["seq_len_dst"]), ref["seq_len_dst"])
+    assert np.array_equal(npy(out["src_of_dst"]), ref["src_of_dst"])
+    assert int(out["n_pages_used"][0]) == ref["n_pages_used"] == n_dst
+    del ref
+    # every layer: destination page j holds source page flat[j]  (holds at any size)
+    flat = bt[surv.long()].reshape(-1).long()
+    for layer in range(cfg.n_layers):
+        for c in range(2):
+            assert torch.equal(dst[layer, c].view(torch.int16), kv[layer, c].view(torch.int16)[flat]), (layer, c)
+    del kv, dst, flat
+    free()
+
+
+@pytest.mark.parametrize("name", BIG)
+def test_logprob_full_size_sampled_rows(A, W, name):
+    """The fused log-prob pass over the configuration's full T x V x d (1.2-2.4 M response tokens), with
+    more than 1,024 rows checked against the float64 oracle, edge rows and edge targets among them."""
+    cfg = W.CONFIGS[name]
+    free()
+    hidden, lm_head, targets, cu = W.logprob_inputs(cfg, DEV)
+    T = hidden.shape[0]
+    say("%s logprob full size: T=%d V=%d d=%d" % (name, T, cfg.vocab, cfg.d))
+    assert cfg.resp_lo * cfg.n_keep <= T <= cfg.resp_hi * cfg.n_keep and lm_head.shape == (cfg.vocab, cfg.d)
+    lp, lse = A.arrol_logprob(hidden, lm_head, targets, want_lse=True)
+    torch.cuda.synchronize()
+    rows = sample_rows(T, 1024, cfg.vocab, targets, cu=cu)
+    must = {0, T - 1, int(cu[1]) - 1, int(cu[-2]), int(cu[-1]) - 1} | {r for r, _ in W.edge_target_rows(T, cfg.vocab)}
+    assert must <= set(rows.tolist()) and len(rows) >= 1024
+    t_s = npy(targets)[rows.numpy()]
+    last_edge = (cfg.vocab - 1) // 256 * 256
+    assert {0, cfg.vocab - 1, 255, 256, last_edge - 1, last_edge} <= set(t_s.tolist())
+    say("%s oracle on %d rows" % (name, len(rows)))
+    lp_o, lse_o = O.logprob(bits(hidden[rows.to(DEV)]), bits(lm_head), t_s)
+    assert np.max(np.abs(npy(lp)[rows.numpy()] - lp_o)) < 1e-4      # the bar is 2e-3; 1e-4 is what fp32 accumulation allows here
+    assert np.max(np.abs(npy(lse)[rows.numpy()] - lse_o)) < 1e-4
+    # whole output: finite, negative, and distributed as logits ~ N(0,1) imply (lse ~ log V + 1/2)
+    assert bool(torch.isfinite(lp).all()) and float(lp.max()) <= 0.0
+    assert abs(float(lse.mean()) - (np.log(cfg.vocab) + 0.5)) < 0.05
+    del hidden, lm_head, lp, lse
+    free()
 
 
 @pytest.mark.parametrize("name,T", [("qwen1p7b", 300), ("llama3b", 257), ("qwen8b", 200)])

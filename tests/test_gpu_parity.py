@@ -219,8 +219,8 @@ def test_compact_out_of_range_indices_are_skipped(A, W):
 
 
 # ------------------------------------------------------------------------------- logprob
-def check_logprob(A, hidden, lm_head, targets, tol=LOGP_DERIVED):
-    lp, lse = A.arrol_logprob(hidden, lm_head, targets, want_lse=True)
+def check_logprob(A, hidden, lm_head, targets, tol=LOGP_DERIVED, n_splits=0):
+    lp, lse = A.arrol_logprob(hidden, lm_head, targets, want_lse=True, n_splits=n_splits)
     torch.cuda.synchronize()
     lp_o, lse_o = O.logprob(bits(hidden), bits(lm_head), npy(targets))
     err = np.max(np.abs(npy(lp).astype(np.float64) - lp_o))
@@ -257,11 +257,7 @@ def test_logprob_independent_of_vocab_splits(A, splits):
     hidden = torch.randn(T, d, generator=g, device=DEV).to(torch.bfloat16)
     lm_head = (torch.randn(V, d, generator=g, device=DEV) * 0.2).to(torch.bfloat16)
     targets = torch.randint(0, V, (T,), generator=g, device=DEV, dtype=torch.int32)
-    try:
-        A.set_tuning("logprob_splits", splits)
-        check_logprob(A, hidden, lm_head, targets)
-    finally:
-        A.set_tuning("logprob_splits", 0)
+    check_logprob(A, hidden, lm_head, targets, n_splits=splits)
 
 
 def test_logprob_extreme_logits_and_bad_target(A):

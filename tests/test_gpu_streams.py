@@ -93,6 +93,36 @@ def test_step_on_a_side_stream_matches_the_default_stream(A, W):
     torch.cuda.synchronize()
 
 
+def test_side_stream_calls_that_allocate_their_own_workspace(A, W):
+    """With workspace=None the binding creates the scratch itself; it must belong to the stream the kernels run
+    on, or the allocator could hand it to the default stream's work below while those kernels still use it."""
+    print("[case] side stream, temporaries created by the binding", flush=True)
+    st = Step(A, W, 2)
+    cfg = st.cfg
+    lp_ref = A.arrol_logprob(st.lp_hidden, st.lm_head, st.targets)
+    out_ref = A.arrol_compact(st.kv_src, st.kv_dst, st.block_table, st.seq_len, st.tokens,
+                              A.arrol_select(A.arrol_score(st.hidden, st.w, st.bias)[1], cfg.n_prompts, cfg.G, cfg.K)[1])
+    torch.cuda.synchronize()
+    kv_ref = st.kv_dst.clone()
+    st.kv_dst.zero_()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()                         # default priority
+    _, q = A.arrol_score(st.hidden, st.w, st.bias, stream=side)
+    _, surv = A.arrol_select(q, cfg.n_prompts, cfg.G, cfg.K, stream=side)
+    out = A.arrol_compact(st.kv_src, st.kv_dst, st.block_table, st.seq_len, st.tokens, surv, stream=side)
+    lp = A.arrol_logprob(st.lp_hidden, st.lm_head, st.targets, stream=side)
+    # default-stream work that allocates and overwrites memory of the sizes just dropped
+    junk = [torch.full((A.arrol_logprob_workspace_bytes(st.lp_hidden.shape[0], cfg.vocab, cfg.d) // 4,), float("nan"),
+                       device=DEV) for _ in range(4)]
+    side.synchronize()
+    assert torch.equal(lp, lp_ref)
+    assert torch.equal(st.kv_dst.view(torch.int16), kv_ref.view(torch.int16))
+    for k in out_ref:
+        assert torch.equal(out[k], out_ref[k]), k
+    del junk
+    torch.cuda.synchronize()
+
+
 def test_step_captured_in_a_graph_replays_on_new_inputs(A, W):
     print("[case] graph capture", flush=True)
     st = Step(A, W, 1)
