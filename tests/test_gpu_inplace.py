@@ -99,3 +99,17 @@ def test_inplace_llama1b_full_size(A, W):
     flat_new = out["block_table_dst"].reshape(-1).long()
     assert int(flat_new.max()) == n_live - 1 and torch.unique(flat_new).numel() == n_live
     assert torch.equal(kv[:, :, flat_new, 0, 0, :4].view(torch.int16), probe.view(torch.int16))
+
+
+def test_inplace_pool_beyond_the_one_launch_planner(A, W):
+    """More than 524,288 pages: the live-page bitmap no longer fits the planning workgroup's LDS and the call
+    falls back to the multi-launch planner (flags in the workspace, single-workgroup scan)."""
+    print("[case] inplace, 600,000-page pool of 16-byte chunks", flush=True)
+    cfg = W.shrink(W.CONFIGS["tiny"], n_prompts=3000, G=4, K=2, head_dim=8, page_tokens=1, ckpt_len=50, n_layers=1,
+                   n_kv_heads=1)
+    kv, bt, sl, _ = W.compact_inputs(cfg, DEV, extra_pages=123, ragged=True)
+    assert kv.shape[2] > 524288
+    g = torch.Generator(device="cpu"); g.manual_seed(5)
+    pick = torch.stack([torch.sort(torch.randperm(cfg.G, generator=g)[:cfg.K])[0] + i * cfg.G
+                        for i in range(cfg.n_prompts)]).reshape(-1).to(torch.int32).to(DEV)
+    run_case(A, kv, bt, sl, pick)
