@@ -35,7 +35,10 @@ ALL_WORKLOADS = ["tiny", "llama1b", "qwen1p7b", "llama3b", "qwen8b"]
 # (hbm_traffic_<workload>.txt).  For the log-prob kernel the figure is the fetch at the L2 <-> fabric
 # interface, Infinity-Cache hits included.  None where not measured.
 PROFILED_TRAFFIC_BYTES = {
-    ("llama1b", "logprob"): 2.7727e11, ("llama1b", "compact"): 8.593e9,
+    ("llama1b", "logprob"): 2.8722e+11, ("llama1b", "compact"): 8.5946e+09,
+    ("qwen1p7b", "logprob"): 1.4491e+12, ("qwen1p7b", "compact"): 1.2027e+11,
+    ("llama3b", "logprob"): 1.8250e+12, ("llama3b", "compact"): 1.2027e+11,
+    ("qwen8b", "logprob"): 5.8557e+12, ("qwen8b", "compact"): 1.5464e+11,
 }
 
 
@@ -380,8 +383,13 @@ def time_extras(A, W, cfg, dev, torch, lp_hidden, lm_head, targets, cu, reps=10)
     w1 = (torch.randn(m, d, generator=g, device=dev) * d ** -0.5).to(torch.bfloat16)
     b1 = torch.zeros(m, device=dev)
     w2 = torch.randn(m, generator=g, device=dev) * m ** -0.5
-    ms = timed(lambda: A.arrol_score_mlp(hidden, w1, b1, w2))
-    out["score_mlp"] = {"ms": ms, "shape": "N=%d, d=%d, m=%d" % (N, d, m), "TFLOPs": 2.0 * N * d * m / ms / 1e9}
+    sws_bytes = A.lib().arrol_score_mlp_workspace_bytes(N, d, m)
+    sws = torch.empty(sws_bytes, dtype=torch.uint8, device=dev) if sws_bytes else None
+    ms = timed(lambda: A.arrol_score_mlp(hidden, w1, b1, w2, workspace=sws))
+    out["score_mlp"] = {"ms": ms, "shape": "N=%d, d=%d, m=%d" % (N, d, m), "TFLOPs": 2.0 * N * d * m / ms / 1e9,
+                        "path": "small-batch (wavefront per 32x32 block + finish)" if sws_bytes else "tile kernel",
+                        "note": "HIP-event mean over back-to-back calls from Python: a floor of ~20 us per call is host launch cost; "
+                                "kernel durations are in profiles/"}
     mws = torch.empty(max(256, A.lib().arrol_score_mlp_grad_workspace_bytes(N, d, m)), dtype=torch.uint8, device=dev)
     ms = timed(lambda: A.arrol_score_mlp_grad(hidden, w1, b1, w2, 0.0, labels, workspace=mws))
     out["score_mlp_grad"] = {"ms": ms, "shape": "N=%d, d=%d, m=%d" % (N, d, m), "TFLOPs": 6.0 * N * d * m / ms / 1e9}

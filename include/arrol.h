@@ -79,10 +79,17 @@ int arrol_score(const void* hidden, int64_t row_stride_elems, const int64_t* row
  * hidden, row_stride_elems, row_index, score_out, prob_out as in arrol_score.
  * w1 bf16 [m, d] row-major, 16-byte aligned; b1 NULL (zero) or fp32 [m]; w2 fp32 [m]; b2 by value; m >= 1.
  * bf16 products accumulated in fp32 on the matrix cores; the [n_rows, m] activations are never stored.
+ * workspace: optional.  With NULL (or fewer than arrol_score_mlp_workspace_bytes(n_rows, d, m) bytes) the
+ * call is one kernel whose workgroups each take 128 rollouts; given the queried size (16-byte aligned) a
+ * small batch (the query returns 0 where this does not apply) is spread over the whole GPU instead - one
+ * wavefront per 32 units x 32 rollouts, partial sums over the units in the workspace, added in a fixed
+ * order by a second launch.  Results of the two paths differ by fp32 summation order only.
  */
+size_t arrol_score_mlp_workspace_bytes(int32_t n_rows, int32_t d, int32_t m);
 int arrol_score_mlp(const void* hidden, int64_t row_stride_elems, const int64_t* row_index,
                     const void* w1, const float* b1, const float* w2, float b2, int32_t n_rows,
-                    int32_t d, int32_t m, float* score_out, float* prob_out, void* stream);
+                    int32_t d, int32_t m, float* score_out, float* prob_out, void* workspace,
+                    size_t workspace_bytes, void* stream);
 
 /*
  * Stage 2 -- per-group keep-K selection by the balance rule (Thm 4.2 / App. A.1):

@@ -44,7 +44,8 @@ _SIGNATURES = {
     "arrol_version": (ctypes.c_int, []),
     "arrol_error_string": (ctypes.c_char_p, [ctypes.c_int]),
     "arrol_score": (ctypes.c_int, [_vp, _i64, _vp, _vp, _f32, _i32, _i32, _vp, _vp, _vp]),
-    "arrol_score_mlp": (ctypes.c_int, [_vp, _i64, _vp, _vp, _vp, _vp, _f32, _i32, _i32, _i32, _vp, _vp, _vp]),
+    "arrol_score_mlp_workspace_bytes": (_sz, [_i32, _i32, _i32]),
+    "arrol_score_mlp": (ctypes.c_int, [_vp, _i64, _vp, _vp, _vp, _vp, _f32, _i32, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
     "arrol_score_grad_workspace_bytes": (_sz, [_i32, _i32]),
     "arrol_score_grad": (ctypes.c_int, [_vp, _i64, _vp, _vp, _f32, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _sz, _vp]),
     "arrol_score_mlp_grad_workspace_bytes": (_sz, [_i32, _i32, _i32]),
@@ -161,8 +162,10 @@ def arrol_score(hidden, w, bias=0.0, row_index=None, out_score=None, out_prob=No
 
 
 @_on_stream
-def arrol_score_mlp(hidden, w1, b1, w2, b2=0.0, row_index=None, stream=None):
-    """hidden bf16 [R, d], w1 bf16 [m, d], b1 fp32 [m] or None, w2 fp32 [m] -> (score, prob) fp32 [n]."""
+def arrol_score_mlp(hidden, w1, b1, w2, b2=0.0, row_index=None, workspace="auto", stream=None):
+    """hidden bf16 [R, d], w1 bf16 [m, d], b1 fp32 [m] or None, w2 fp32 [m] -> (score, prob) fp32 [n].
+    workspace: "auto" allocates what the library asks for (the small-batch path), None passes none (the
+    one-launch kernel), or a uint8 tensor."""
     if hidden.dim() != 2 or hidden.dtype != torch.bfloat16 or not hidden.is_cuda or hidden.stride(1) != 1:
         raise TypeError("hidden must be a 2-D bf16 GPU tensor with contiguous rows")
     d = hidden.shape[1]
@@ -173,10 +176,14 @@ def arrol_score_mlp(hidden, w1, b1, w2, b2=0.0, row_index=None, stream=None):
     dev = hidden.device
     score = torch.empty(n, dtype=torch.float32, device=dev)
     prob = torch.empty(n, dtype=torch.float32, device=dev)
+    if isinstance(workspace, str):
+        need = lib().arrol_score_mlp_workspace_bytes(n, d, m)
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev) if need else None
     row_stride = hidden.stride(0) if hidden.shape[0] > 1 else max(d, hidden.stride(0))
     rc = lib().arrol_score_mlp(hidden.data_ptr(), row_stride, _ptr(row_index, torch.int64, "row_index"),
                                _ptr(w1, torch.bfloat16, "w1"), _ptr(b1, torch.float32, "b1"),
                                _ptr(w2, torch.float32, "w2"), float(b2), n, d, m, score.data_ptr(), prob.data_ptr(),
+                               _ptr(workspace, torch.uint8, "workspace"), workspace.numel() if workspace is not None else 0,
                                _stream(stream))
     _check("arrol_score_mlp", rc)
     return score, prob

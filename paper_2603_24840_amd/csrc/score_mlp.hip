@@ -320,6 +320,98 @@ __global__ __launch_bounds__(kThreads) void score_mlp_kernel(MlpArgs a) {
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Small batches (a few hundred rollouts): the tile kernel above would run on n_rows / 128 compute units and
+// each of them would walk all of K behind a three-stage ring (bytes in flight over memory latency: ~90 us
+// for 512 x 2048 x 512).  Here every wavefront owns one 32-unit x 32-rollout block of the pre-activations
+// over the whole K, n_rows/32 x m/32 wavefronts in all, and takes its MFMA fragments straight from global
+// memory: no LDS, no barrier, kSmallDepth K64 blocks (2 x 4 x 16 bytes per lane each) in flight per lane,
+// one wavefront per workgroup.
+// The contraction does not care in which order K is visited, so a lane loads 64 CONTIGUOUS bytes of its row
+// per K64 block (lane half lh takes k in [32 lh, 32 lh + 32)) and the q-th 16 bytes feed the q-th MFMA of
+// the block, the same assignment on both operands.  Each wavefront writes sum_u w2[u] relu(pre[u] + b1[u])
+// over its 32 units to partial[unit block][rollout]; a second kernel adds the unit blocks in index order.
+constexpr int kSmallMaxRows = 4096;     // beyond this the tile kernel has enough workgroups of its own
+constexpr int kSmallDepth = 4;          // K64 blocks in flight
+constexpr int kSmallThreads = 64;       // one wavefront per workgroup: its lanes address 64 different cache lines per
+                                        // load, so the texture addresser of a compute unit is the resource to spread over
+
+__global__ __launch_bounds__(kSmallThreads) void score_mlp_small_kernel(
+    const uint16_t* __restrict__ hidden, int64_t row_stride, const int64_t* __restrict__ row_index,
+    const uint16_t* __restrict__ w1, const float* __restrict__ b1, const float* __restrict__ w2, int n_rows, int d, int m,
+    int n_ub, float* __restrict__ partial) {
+    const int lane = threadIdx.x & 63;
+    const int l31 = lane & 31, lh = lane >> 5;
+    const int ub = blockIdx.y;                      // unit block
+    const int r0 = blockIdx.x * 32, u0 = ub * 32;
+    int row = r0 + l31;
+    row = row < n_rows ? row : n_rows - 1;
+    int unit = u0 + l31;
+    unit = unit < m ? unit : m - 1;
+    const int64_t src = row_index ? row_index[row] : row;
+    const uint4* hp = reinterpret_cast<const uint4*>(hidden + src * row_stride + lh * 32);
+    const uint4* wp = reinterpret_cast<const uint4*>(w1 + static_cast<int64_t>(unit) * d + lh * 32);
+    const int n_kb = d / 64;                        // host: d is a multiple of 64
+    uint4 fa[kSmallDepth][4], fb[kSmallDepth][4];
+    auto load_block = [&](int slot, int kb) {       // 8 uint4 = one K64 block of this lane's two rows
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            fa[slot][q] = wp[kb * 8 + q];
+            fb[slot][q] = hp[kb * 8 + q];
+        }
+    };
+#pragma unroll
+    for (int s = 0; s < kSmallDepth; ++s)
+        if (s < n_kb) load_block(s, s);
+    f32x16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    for (int kb0 = 0; kb0 < n_kb; kb0 += kSmallDepth) {
+#pragma unroll
+        for (int s = 0; s < kSmallDepth; ++s) {
+            const int kb = kb0 + s;
+            if (kb < n_kb) {                        // wave-uniform
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[s][q]),
+                                                                  __builtin_bit_cast(bf16x8, fb[s][q]), acc, 0, 0, 0);
+                if (kb + kSmallDepth < n_kb) load_block(s, kb + kSmallDepth);
+            }
+        }
+    }
+    // acc[v] = pre-activation of unit u0 + (v/4)*8 + lh*4 + v%4 for rollout r0 + l31
+    float part = 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int u = u0 + (v >> 2) * 8 + lh * 4 + (v & 3);
+        const bool live = u < m;
+        const float bias = (live && b1) ? b1[u] : 0.f;
+        const float w = live ? w2[u] : 0.f;
+        part = fmaf(fmaxf(acc[v] + bias, 0.f), w, part);
+    }
+    part += __shfl_xor(part, 32, ARROL_WAVE);       // the two lane halves hold different units of one rollout
+    if (lh == 0 && r0 + l31 < n_rows) partial[static_cast<int64_t>(ub) * n_rows + r0 + l31] = part;
+}
+
+__global__ __launch_bounds__(256) void score_mlp_small_finish_kernel(const float* __restrict__ partial, int n_ub,
+                                                                     int n_rows, float b2, float* __restrict__ score_out,
+                                                                     float* __restrict__ prob_out) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n_rows) return;
+    float s = 0.f;
+    for (int ub = 0; ub < n_ub; ++ub) s += partial[static_cast<int64_t>(ub) * n_rows + i];
+    s += b2;
+    float q;
+    if (s >= 0.f) {
+        q = 1.f / (1.f + expf(-s));
+    } else {
+        const float e = expf(s);
+        q = e / (1.f + e);
+    }
+    if (score_out) score_out[i] = s;
+    prob_out[i] = q;
+}
+
 // r_i = (q_i - y_i) / N and the loss, one workgroup, fixed summation order
 __global__ __launch_bounds__(1024) void mlp_residual_kernel(const float* __restrict__ score,
                                                             const float* __restrict__ prob,
@@ -374,7 +466,7 @@ __global__ __launch_bounds__(256) void mlp_transpose_kernel(const uint16_t* __re
 
 struct GradPlan {
     int n_rb, n_pad, n_cb, n_groups, n_kc, splits, kc_per_split;
-    size_t off_score, off_prob, off_resid, off_ht, off_dt, off_unit, off_slab, total;
+    size_t off_score, off_prob, off_resid, off_ht, off_dt, off_unit, off_slab, off_small, total;
 };
 
 size_t align256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
@@ -402,6 +494,8 @@ GradPlan make_grad_plan(int n_rows, int d, int m) {
     p.off_unit = o;  o = align256(o + sizeof(float) * static_cast<size_t>(p.n_rb) * 2 * m);
     p.off_slab = o;
     if (p.splits > 1) o = align256(o + sizeof(float) * static_cast<size_t>(p.splits) * m * d);
+    p.off_small = o;                      // partial scores of the small-batch forward pass
+    if (n_rows <= kSmallMaxRows && d % 64 == 0) o = align256(o + sizeof(float) * static_cast<size_t>((m + 31) / 32) * n_rows);
     p.total = o;
     return p;
 }
@@ -421,17 +515,38 @@ int launch_mlp(const MlpArgs& a, dim3 grid, hipStream_t st) {
 
 }  // namespace
 
+extern "C" size_t arrol_score_mlp_workspace_bytes(int32_t n_rows, int32_t d, int32_t m) {
+    if (n_rows < 1 || d < 8 || m < 1) return 0;
+    if (n_rows > kSmallMaxRows || d % 64) return 0;   // the one-launch tile kernel needs no scratch
+    return align256(sizeof(float) * static_cast<size_t>((m + 31) / 32) * n_rows);
+}
+
 extern "C" int arrol_score_mlp(const void* hidden, int64_t row_stride_elems, const int64_t* row_index,
                                const void* w1, const float* b1, const float* w2, float b2, int32_t n_rows,
-                               int32_t d, int32_t m, float* score_out, float* prob_out, void* stream) {
+                               int32_t d, int32_t m, float* score_out, float* prob_out, void* workspace,
+                               size_t workspace_bytes, void* stream) {
     if (n_rows < 0 || d < 8 || (d & 7) || m < 1 || row_stride_elems < d || (row_stride_elems & 7)) return ARROL_EINVAL;
     if (n_rows == 0) return ARROL_OK;
     if (!hidden || !w1 || !w2 || !prob_out || !arrol_aligned16(hidden) || !arrol_aligned16(w1)) return ARROL_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const size_t need = arrol_score_mlp_workspace_bytes(n_rows, d, m);
+    if (need > 0 && workspace && arrol_aligned16(workspace) && workspace_bytes >= need) {
+        // small batch: one wavefront per 32 x 32 block of pre-activations, then the sum over the unit blocks
+        const int n_ub = (m + 31) / 32;
+        float* partial = static_cast<float*>(workspace);
+        arrol_launch(score_mlp_small_kernel, dim3((n_rows + 31) / 32, n_ub), dim3(kSmallThreads), 0, st,
+                     static_cast<const uint16_t*>(hidden), row_stride_elems, row_index, static_cast<const uint16_t*>(w1),
+                     b1, w2, n_rows, d, m, n_ub, partial);
+        if (arrol_launch_failed()) return arrol_launch_status();
+        arrol_launch(score_mlp_small_finish_kernel, dim3((n_rows + 255) / 256), dim3(256), 0, st, partial, n_ub,
+                     n_rows, b2, score_out, prob_out);
+        return arrol_launch_status();
+    }
     MlpArgs a = {};
     a.hidden = static_cast<const uint16_t*>(hidden); a.row_stride = row_stride_elems; a.row_index = row_index;
     a.w1 = static_cast<const uint16_t*>(w1); a.a_stride = d; a.b1 = b1; a.w2 = w2; a.b2 = b2;
     a.n_rows = n_rows; a.d = d; a.m = m; a.score_out = score_out; a.prob_out = prob_out;
-    return launch_mlp<kForward>(a, dim3((n_rows + BR - 1) / BR), static_cast<hipStream_t>(stream));
+    return launch_mlp<kForward>(a, dim3((n_rows + BR - 1) / BR), st);
 }
 
 extern "C" size_t arrol_score_mlp_grad_workspace_bytes(int32_t n_rows, int32_t d, int32_t m) {
@@ -477,8 +592,19 @@ extern "C" int arrol_score_mlp_grad(const void* hidden, int64_t row_stride_elems
     a.hidden = static_cast<const uint16_t*>(hidden); a.row_stride = row_stride_elems; a.row_index = row_index;
     a.w1 = static_cast<const uint16_t*>(w1); a.a_stride = d; a.b1 = b1; a.w2 = w2; a.b2 = b2;
     a.n_rows = n_rows; a.d = d; a.m = m; a.score_out = score; a.prob_out = prob;
-    int rc = launch_mlp<kForward>(a, dim3(p.n_rb), st);
-    if (rc != ARROL_OK) return rc;
+    int rc = ARROL_OK;
+    if (p.total > p.off_small) {          // small batch: the wavefront-per-block forward pass
+        const int n_ub = (m + 31) / 32;
+        float* partial = reinterpret_cast<float*>(ws + p.off_small);
+        arrol_launch(score_mlp_small_kernel, dim3((n_rows + 31) / 32, n_ub), dim3(kSmallThreads), 0, st,
+                     a.hidden, row_stride_elems, row_index, a.w1, b1, w2, n_rows, d, m, n_ub, partial);
+        arrol_launch(score_mlp_small_finish_kernel, dim3((n_rows + 255) / 256), dim3(256), 0, st, partial, n_ub,
+                     n_rows, b2, score, prob);
+        if (arrol_launch_failed()) return arrol_launch_status();
+    } else {
+        rc = launch_mlp<kForward>(a, dim3(p.n_rb), st);
+        if (rc != ARROL_OK) return rc;
+    }
     arrol_launch(mlp_residual_kernel, dim3(1), dim3(1024), 0, st, score, prob, labels, n_rows, resid, loss_out,
                        grad_b2);
     // delta^T and the per-unit sums

@@ -30,7 +30,7 @@ def test_header_declares_the_five_stage_calls():
                "arrol_compact_workspace_bytes", "arrol_logprob_workspace_bytes", "arrol_version",
                "arrol_error_string", "arrol_histogram", "arrol_calibrate",
                "arrol_prune_bernoulli", "arrol_compact_static", "arrol_compact_inplace", "arrol_compact_inplace_workspace_bytes",
-               "arrol_score_mlp", "arrol_score_grad", "arrol_score_grad_workspace_bytes", "arrol_adamw_step", "arrol_score_mlp_grad",
+               "arrol_score_mlp", "arrol_score_mlp_workspace_bytes", "arrol_score_grad", "arrol_score_grad_workspace_bytes", "arrol_adamw_step", "arrol_score_mlp_grad",
                "arrol_score_mlp_grad_workspace_bytes", "arrol_token_confidence",
                "arrol_token_confidence_workspace_bytes", "arrol_trace_confidence",
                "arrol_trace_confidence_workspace_bytes", "arrol_grpo_advantage", "arrol_grpo_objective",
@@ -112,10 +112,14 @@ def test_bad_arguments_are_rejected_on_the_host(pkg):
     big = (fake, fake, 4, None, 0, fake, 1 << 20, 16384, fake, fake, None, fake, fake)
     assert L.arrol_compact_static(fake, lay, far, lay, *big, None) == -2
     # MLP head: bad d, m < 1, null weights
-    assert L.arrol_score_mlp(fake, 16, None, fake, None, fake, 0.0, 4, 12, 8, None, fake, None) == -1
-    assert L.arrol_score_mlp(fake, 16, None, fake, None, fake, 0.0, 4, 16, 0, None, fake, None) == -1
-    assert L.arrol_score_mlp(fake, 16, None, fake, None, None, 0.0, 4, 16, 8, None, fake, None) == -1
-    assert L.arrol_score_mlp(None, 16, None, None, None, None, 0.0, 0, 16, 8, None, None, None) == 0
+    assert L.arrol_score_mlp(fake, 16, None, fake, None, fake, 0.0, 4, 12, 8, None, fake, None, 0, None) == -1
+    assert L.arrol_score_mlp(fake, 16, None, fake, None, fake, 0.0, 4, 16, 0, None, fake, None, 0, None) == -1
+    assert L.arrol_score_mlp(fake, 16, None, fake, None, None, 0.0, 4, 16, 8, None, fake, None, 0, None) == -1
+    assert L.arrol_score_mlp(None, 16, None, None, None, None, 0.0, 0, 16, 8, None, None, None, 0, None) == 0
+    # the small-batch scratch: partial sums per 32-unit block; none beyond 4,096 rows or when d % 64 != 0
+    assert L.arrol_score_mlp_workspace_bytes(512, 2048, 512) >= 16 * 512 * 4
+    assert L.arrol_score_mlp_workspace_bytes(512, 2056, 512) == 0
+    assert L.arrol_score_mlp_workspace_bytes(32768, 4096, 512) == 0
     # head training: bad d, missing gradient output, workspace; optimizer: bad step / betas
     assert L.arrol_score_grad(fake, 16, None, fake, 0.0, fake, 4, 12, None, fake, None, fake, 1 << 20, None) == -1
     assert L.arrol_score_grad(fake, 16384, None, fake, 0.0, fake, 4, 16384, None, fake, None, fake, 1 << 20, None) == -1
