@@ -16,11 +16,12 @@
 //           contiguous K" product, with A = delta^T [m, N] and B = H^T [d, N] (transposed once into the
 //           workspace), fp32 tile stores, optionally split over K with partial slabs added in a fixed order.
 #include "common.h"
+#include "ring_nt.h"
 
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
+using ring_nt::bf16x8;
+using ring_nt::f32x16;
 
 constexpr int kThreads = 256;
 constexpr int BU = 256;   // hidden units per pass
@@ -412,21 +413,161 @@ __global__ __launch_bounds__(256) void score_mlp_small_finish_kernel(const float
     prob_out[i] = q;
 }
 
-// r_i = (q_i - y_i) / N and the loss, one workgroup, fixed summation order
+// ---------------------------------------------------------------------------------------------------------
+// Large batches (more than kSmallMaxRows rollouts, d a multiple of 64, rows addressed without row_index):
+// the same three contractions on the 8-wavefront direct-to-LDS ring pipeline of ring_nt.h, one 256 x 256
+// accumulator tile per workgroup: grid = (blocks of 256 B rows, tiles of 256 A rows, K splits).
+//   forward  A = W1 [m, d], B = hidden [N, d]: bias + ReLU + w2 dot per rollout (lane-local over the
+//            units), partial scores [unit tile][rollout] to the workspace, summed by the finish kernel;
+//   delta    same product; delta^T (bf16, unit-major) and the per-unit sums over each wavefront's 64 rollouts
+//            to unit_partial[(block * 4 + wave column)][2][m];
+//   wgrad    A = delta^T [m, n_pad], B = H^T [d, n_pad] over K = rollouts (split): fp32 tile stores.
+using RingCfg = ring_nt::RingTile<256, 256, 2, 4>;
+
+struct MlpRingArgs {
+    const uint16_t* a; unsigned a_stride;   // A rows (bytes between rows), a_rows of them
+    const uint16_t* b; unsigned b_stride;   // B rows, b_rows of them
+    int a_rows, b_rows, n_k64, k64_per_split;
+    const float* b1; const float* w2;
+    float* partial;              // forward: [gridDim.y][b_rows]
+    const float* resid;          // delta: [b_rows]
+    uint16_t* delta_t; int64_t delta_stride; float* unit_partial;   // delta^T has delta_stride columns (zero beyond b_rows)
+    float* c_out; int64_t c_stride;         // wgrad: [gridDim.z][a_rows][c_stride]
+};
+
+template <int MODE>
+__global__ __launch_bounds__(RingCfg::NT) void mlp_ring_kernel(MlpRingArgs a) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    using C = RingCfg;
+    constexpr int BM = C::BM, BN = C::BN, TM = C::TM, TN = C::TN;
+    const int tb = blockIdx.x, vt = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / C::WN, wn = wave % C::WN;
+    const int l31 = lane & 31, lh = lane >> 5;
+    const int k64_lo = MODE == kWgrad ? static_cast<int>(blockIdx.z) * a.k64_per_split : 0;
+    const int k64_hi = MODE == kWgrad ? (k64_lo + a.k64_per_split < a.n_k64 ? k64_lo + a.k64_per_split : a.n_k64) : a.n_k64;
+
+    ring_nt::Walk w;
+    w.a_base = reinterpret_cast<const char*>(a.a) + static_cast<int64_t>(vt) * BM * a.a_stride + static_cast<int64_t>(k64_lo) * 128;
+    w.b_base = reinterpret_cast<const char*>(a.b) + static_cast<int64_t>(tb) * BN * a.b_stride + static_cast<int64_t>(k64_lo) * 128;
+    w.a_stride = a.a_stride;
+    w.b_stride = a.b_stride;
+    w.a_rows = a.a_rows - vt * BM;
+    w.b_rows = a.b_rows - tb * BN < BN ? a.b_rows - tb * BN : BN;
+    w.n_tiles = 1;
+    w.n_k64 = k64_hi - k64_lo;
+
+    const int unit0 = vt * BM + wm * (BM / C::WM);           // first A row of this wavefront
+    const int row0 = tb * BN + wn * (BN / C::WN);            // first B row of this wavefront
+    float part[TN] = {0.f, 0.f};
+    float resid[TN] = {0.f, 0.f};
+    if (MODE == kDelta) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int r = row0 + j * 32 + l31;
+            resid[j] = r < a.b_rows ? a.resid[r] : 0.f;
+        }
+    }
+    f32x16 acc[TM][TN];
+    ring_nt::walk<C>(w, lds, acc, [](f32x16 (&)[TM][TN], int) {});   // one tile: the epilogue runs here, after the walk
+    {
+        // acc[i][j][v]: A row unit0 + i*32 + (v/4)*8 + lh*4 + v%4, B row row0 + j*32 + l31
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int u = unit0 + i * 32 + (v >> 2) * 8 + lh * 4 + (v & 3);
+                const bool live = u < a.a_rows;
+                if (MODE == kWgrad) {
+                    float* crow = a.c_out + (static_cast<int64_t>(blockIdx.z) * a.a_rows + u) * a.c_stride;
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        const int col = row0 + j * 32 + l31;
+                        if (live && col < a.b_rows) crow[col] = acc[i][j][v];
+                        acc[i][j][v] = 0.f;
+                    }
+                } else {
+                    const float bias = (live && a.b1) ? a.b1[u] : 0.f;
+                    const float wu = live ? a.w2[u] : 0.f;
+                    if (MODE == kForward) {
+#pragma unroll
+                        for (int j = 0; j < TN; ++j) {
+                            part[j] = fmaf(fmaxf(acc[i][j][v] + bias, 0.f), wu, part[j]);
+                            acc[i][j][v] = 0.f;
+                        }
+                    } else {
+                        float gw = 0.f, gb = 0.f;
+                        uint16_t* drow = a.delta_t + static_cast<int64_t>(live ? u : 0) * a.delta_stride + row0 + l31;
+#pragma unroll
+                        for (int j = 0; j < TN; ++j) {
+                            const float pre = acc[i][j][v] + bias;
+                            const float dl = pre > 0.f ? resid[j] * wu : 0.f;
+                            gw = fmaf(resid[j], fmaxf(pre, 0.f), gw);
+                            gb += dl;
+                            if (live && row0 + j * 32 + l31 < a.delta_stride) drow[j * 32] = f32_to_bf16_rne(dl);   // 0 in the padding
+                            acc[i][j][v] = 0.f;
+                        }
+                        // sum over the 32 rollout lanes of this half-wave (both halves run the same steps)
+#pragma unroll
+                        for (int msk = 16; msk >= 1; msk >>= 1) {
+                            gw += __shfl_xor(gw, msk, ARROL_WAVE);
+                            gb += __shfl_xor(gb, msk, ARROL_WAVE);
+                        }
+                        if (live && l31 == 0) {
+                            float* up = a.unit_partial + static_cast<int64_t>(tb * C::WN + wn) * 2 * a.a_rows;
+                            up[u] = gw;
+                            up[a.a_rows + u] = gb;
+                        }
+                    }
+                }
+            }
+    }
+    if (MODE != kForward) return;
+    // the two lane halves and the two wavefront rows hold different units of the same rollouts
+    float* red = reinterpret_cast<float*>(lds);   // [WM][BN]
+#pragma unroll
+    for (int j = 0; j < TN; ++j) part[j] += __shfl_xor(part[j], 32, ARROL_WAVE);
+    if (lh == 0) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) red[wm * BN + wn * (BN / C::WN) + j * 32 + l31] = part[j];
+    }
+    __syncthreads();
+    for (int col = tid; col < BN; col += C::NT) {
+        const int r = tb * BN + col;
+        if (r < a.b_rows) a.partial[static_cast<int64_t>(vt) * a.b_rows + r] = red[col] + red[BN + col];
+    }
+}
+
+template <int MODE>
+int launch_mlp_ring(const MlpRingArgs& a, dim3 grid, hipStream_t st) {
+    static arrol_device_flags ok;
+    if (!arrol_allow_lds(&mlp_ring_kernel<MODE>, RingCfg::LDS_BYTES, ok)) return ARROL_EHIP;
+    arrol_launch(mlp_ring_kernel<MODE>, grid, dim3(RingCfg::NT), RingCfg::LDS_BYTES, st, a);
+    return ARROL_OK;
+}
+
+// the ring kernels address a lane's row with a 32-bit byte offset inside a 256-row tile
+bool ring_applies(int n_rows, int d, int64_t row_stride_elems, const int64_t* row_index) {
+    return n_rows > kSmallMaxRows && d % 64 == 0 && row_index == nullptr && row_stride_elems * 2 * 256 < (1ll << 31);
+}
+
+// r_i = (q_i - y_i) / N and the loss: one workgroup per 1024 rows writes its two partial sums, the second
+// kernel adds them in block order (fixed summation order, bit-reproducible)
 __global__ __launch_bounds__(1024) void mlp_residual_kernel(const float* __restrict__ score,
                                                             const float* __restrict__ prob,
                                                             const float* __restrict__ labels, int n_rows,
-                                                            float* __restrict__ resid, float* __restrict__ loss_out,
-                                                            float* __restrict__ grad_b2) {
+                                                            float* __restrict__ resid, float* __restrict__ block_sums) {
     __shared__ float red[2][16];
     const float inv_n = 1.f / static_cast<float>(n_rows);
     float loss = 0.f, rs = 0.f;
-    for (int i = threadIdx.x; i < n_rows; i += 1024) {
+    const int i = blockIdx.x * 1024 + threadIdx.x;
+    if (i < n_rows) {
         const float s = score[i], y = labels[i];
         const float r = (prob[i] - y) * inv_n;
         resid[i] = r;
-        rs += r;
-        loss += fmaxf(s, 0.f) - y * s + log1pf(expf(-fabsf(s)));
+        rs = r;
+        loss = fmaxf(s, 0.f) - y * s + log1pf(expf(-fabsf(s)));
     }
     loss = wave_sum_f32(loss);
     rs = wave_sum_f32(rs);
@@ -436,37 +577,56 @@ __global__ __launch_bounds__(1024) void mlp_residual_kernel(const float* __restr
     if (threadIdx.x == 0) {
         float a = 0.f, b = 0.f;
         for (int w = 0; w < 16; ++w) { a += red[0][w]; b += red[1][w]; }
-        if (loss_out) *loss_out = a * inv_n;
-        if (grad_b2) *grad_b2 = b;
+        block_sums[blockIdx.x] = a;
+        block_sums[gridDim.x + blockIdx.x] = b;
     }
 }
 
-// out[c][i] = hidden[row(i)][c] for i < n_rows, 0 for n_rows <= i < n_pad: 64 x 64 tiles through LDS
+__global__ void mlp_residual_finish_kernel(const float* __restrict__ block_sums, int n_blocks, int n_rows,
+                                           float* __restrict__ loss_out, float* __restrict__ grad_b2) {
+    float a = 0.f, b = 0.f;
+    for (int k = 0; k < n_blocks; ++k) { a += block_sums[k]; b += block_sums[n_blocks + k]; }
+    if (loss_out) *loss_out = a / static_cast<float>(n_rows);
+    if (grad_b2) *grad_b2 = b;
+}
+
+// out[c][i] = hidden[row(i)][c] for i < n_rows, 0 for n_rows <= i < n_pad: 64 x 64 tiles through LDS, 16 bytes
+// per lane on both sides (8 lanes cover the 128 bytes a tile row has in the source and in the destination)
 __global__ __launch_bounds__(256) void mlp_transpose_kernel(const uint16_t* __restrict__ hidden, int64_t row_stride,
                                                             const int64_t* __restrict__ row_index, int n_rows,
                                                             int d, int n_pad, uint16_t* __restrict__ out) {
-    __shared__ uint16_t tile[64][66];
+    __shared__ __attribute__((aligned(16))) uint16_t tile_t[64][72];   // [column][rollout], 144-byte pitch
     const int i0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    for (int r = ty; r < 64; r += 4) {
-        const int i = i0 + r, c = c0 + tx;
-        uint16_t v = 0;
-        if (i < n_rows && c < d) {
+    const int chunk = threadIdx.x & 7, r8 = threadIdx.x >> 3;           // 32 rows x 8 chunks per pass
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const int r = r8 + p * 32, i = i0 + r, c = c0 + chunk * 8;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (i < n_rows && c < d) {      // d is a multiple of 8: a chunk is inside the row or outside it
             const int64_t src = row_index ? row_index[i] : i;
-            v = hidden[src * row_stride + c];
+            v = *reinterpret_cast<const uint4*>(hidden + src * row_stride + c);
         }
-        tile[r][tx] = v;
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            tile_t[chunk * 8 + 2 * q][r] = static_cast<uint16_t>(w[q] & 0xffffu);
+            tile_t[chunk * 8 + 2 * q + 1][r] = static_cast<uint16_t>(w[q] >> 16);
+        }
     }
     __syncthreads();
-    for (int r = ty; r < 64; r += 4) {
-        const int c = c0 + r, i = i0 + tx;
-        if (c < d && i < n_pad) out[static_cast<int64_t>(c) * n_pad + i] = tile[tx][r];
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const int cr = r8 + p * 32, c = c0 + cr, i = i0 + chunk * 8;
+        if (c < d && i < n_pad)          // n_pad is a multiple of 64: whole chunks
+            *reinterpret_cast<uint4*>(out + static_cast<int64_t>(c) * n_pad + i) =
+                *reinterpret_cast<const uint4*>(&tile_t[cr][chunk * 8]);
     }
 }
 
 struct GradPlan {
     int n_rb, n_pad, n_cb, n_groups, n_kc, splits, kc_per_split;
-    size_t off_score, off_prob, off_resid, off_ht, off_dt, off_unit, off_slab, off_small, total;
+    int r_cb, r_vt, r_splits, r_k64_per_split;
+    size_t off_score, off_prob, off_resid, off_bsum, off_ht, off_dt, off_unit, off_slab, off_small, off_rslab, total;
 };
 
 size_t align256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
@@ -489,13 +649,30 @@ GradPlan make_grad_plan(int n_rows, int d, int m) {
     p.off_score = o; o = align256(o + sizeof(float) * n_rows);
     p.off_prob = o;  o = align256(o + sizeof(float) * n_rows);
     p.off_resid = o; o = align256(o + sizeof(float) * n_rows);
+    p.off_bsum = o;  o = align256(o + sizeof(float) * 2 * ((n_rows + 1023) / 1024));
     p.off_ht = o;    o = align256(o + sizeof(uint16_t) * static_cast<size_t>(d) * p.n_pad);
     p.off_dt = o;    o = align256(o + sizeof(uint16_t) * static_cast<size_t>(m) * p.n_pad);
-    p.off_unit = o;  o = align256(o + sizeof(float) * static_cast<size_t>(p.n_rb) * 2 * m);
+    // per-unit partial sums: one row per 128 rollouts (tile kernel) or per 64 (ring kernel's wavefront columns)
+    const int unit_rows = p.n_rb > 4 * ((n_rows + 255) / 256) ? p.n_rb : 4 * ((n_rows + 255) / 256);
+    p.off_unit = o;  o = align256(o + sizeof(float) * static_cast<size_t>(unit_rows) * 2 * m);
     p.off_slab = o;
     if (p.splits > 1) o = align256(o + sizeof(float) * static_cast<size_t>(p.splits) * m * d);
-    p.off_small = o;                      // partial scores of the small-batch forward pass
-    if (n_rows <= kSmallMaxRows && d % 64 == 0) o = align256(o + sizeof(float) * static_cast<size_t>((m + 31) / 32) * n_rows);
+    p.off_small = o;                      // partial scores of the small-batch / ring forward pass
+    if (d % 64 == 0) {
+        const size_t blocks = n_rows <= kSmallMaxRows ? (m + 31) / 32 : (m + 255) / 256;
+        o = align256(o + sizeof(float) * blocks * n_rows);
+    }
+    // ring wgrad: 256-column blocks; K split so that about 256 workgroups run, at most 8 partial slabs
+    p.r_cb = (d + 255) / 256;
+    p.r_vt = (m + 255) / 256;
+    int rs = 256 / (p.r_cb * p.r_vt);
+    if (rs > p.n_kc / 8) rs = p.n_kc / 8;
+    if (rs > 8) rs = 8;
+    if (rs < 1) rs = 1;
+    p.r_k64_per_split = (p.n_kc + rs - 1) / rs;
+    p.r_splits = (p.n_kc + p.r_k64_per_split - 1) / p.r_k64_per_split;
+    p.off_rslab = o;
+    if (n_rows > kSmallMaxRows && d % 64 == 0 && p.r_splits > 1) o = align256(o + sizeof(float) * static_cast<size_t>(p.r_splits) * m * d);
     p.total = o;
     return p;
 }
@@ -517,8 +694,9 @@ int launch_mlp(const MlpArgs& a, dim3 grid, hipStream_t st) {
 
 extern "C" size_t arrol_score_mlp_workspace_bytes(int32_t n_rows, int32_t d, int32_t m) {
     if (n_rows < 1 || d < 8 || m < 1) return 0;
-    if (n_rows > kSmallMaxRows || d % 64) return 0;   // the one-launch tile kernel needs no scratch
-    return align256(sizeof(float) * static_cast<size_t>((m + 31) / 32) * n_rows);
+    if (d % 64) return 0;   // the one-launch tile kernel needs no scratch
+    const size_t blocks = n_rows <= kSmallMaxRows ? (m + 31) / 32 : (m + 255) / 256;   // unit blocks of the two paths
+    return align256(sizeof(float) * blocks * n_rows);
 }
 
 extern "C" int arrol_score_mlp(const void* hidden, int64_t row_stride_elems, const int64_t* row_index,
@@ -530,7 +708,22 @@ extern "C" int arrol_score_mlp(const void* hidden, int64_t row_stride_elems, con
     if (!hidden || !w1 || !w2 || !prob_out || !arrol_aligned16(hidden) || !arrol_aligned16(w1)) return ARROL_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const size_t need = arrol_score_mlp_workspace_bytes(n_rows, d, m);
-    if (need > 0 && workspace && arrol_aligned16(workspace) && workspace_bytes >= need) {
+    if (need > 0 && workspace && arrol_aligned16(workspace) && workspace_bytes >= need &&
+        ring_applies(n_rows, d, row_stride_elems, row_index)) {
+        // large batch: one 256 x 256 tile per workgroup on the ring pipeline, then the sum over the unit tiles
+        const int n_vt = (m + 255) / 256;
+        MlpRingArgs r = {};
+        r.a = static_cast<const uint16_t*>(w1); r.a_stride = static_cast<unsigned>(d) * 2; r.a_rows = m;
+        r.b = static_cast<const uint16_t*>(hidden); r.b_stride = static_cast<unsigned>(row_stride_elems * 2); r.b_rows = n_rows;
+        r.n_k64 = d / 64; r.b1 = b1; r.w2 = w2; r.partial = static_cast<float*>(workspace);
+        const int rc = launch_mlp_ring<kForward>(r, dim3((n_rows + 255) / 256, n_vt), st);
+        if (rc != ARROL_OK) return rc;
+        if (arrol_launch_failed()) return arrol_launch_status();
+        arrol_launch(score_mlp_small_finish_kernel, dim3((n_rows + 255) / 256), dim3(256), 0, st, r.partial, n_vt,
+                     n_rows, b2, score_out, prob_out);
+        return arrol_launch_status();
+    }
+    if (need > 0 && n_rows <= kSmallMaxRows && workspace && arrol_aligned16(workspace) && workspace_bytes >= need) {
         // small batch: one wavefront per 32 x 32 block of pre-activations, then the sum over the unit blocks
         const int n_ub = (m + 31) / 32;
         float* partial = static_cast<float*>(workspace);
@@ -582,11 +775,51 @@ extern "C" int arrol_score_mlp_grad(const void* hidden, int64_t row_stride_elems
     float* score = reinterpret_cast<float*>(ws + p.off_score);
     float* prob = reinterpret_cast<float*>(ws + p.off_prob);
     float* resid = reinterpret_cast<float*>(ws + p.off_resid);
+    float* bsum = reinterpret_cast<float*>(ws + p.off_bsum);
+    const int n_rblocks = (n_rows + 1023) / 1024;
     uint16_t* ht = reinterpret_cast<uint16_t*>(ws + p.off_ht);
     uint16_t* dt = reinterpret_cast<uint16_t*>(ws + p.off_dt);
     float* unit = reinterpret_cast<float*>(ws + p.off_unit);
     float* slab = reinterpret_cast<float*>(ws + p.off_slab);
 
+    if (ring_applies(n_rows, d, row_stride_elems, row_index)) {
+        // large batch: every contraction on the ring pipeline
+        const int n_tb = (n_rows + 255) / 256;
+        float* partial = reinterpret_cast<float*>(ws + p.off_small);
+        MlpRingArgs r = {};
+        r.a = static_cast<const uint16_t*>(w1); r.a_stride = static_cast<unsigned>(d) * 2; r.a_rows = m;
+        r.b = static_cast<const uint16_t*>(hidden); r.b_stride = static_cast<unsigned>(row_stride_elems * 2); r.b_rows = n_rows;
+        r.n_k64 = d / 64; r.b1 = b1; r.w2 = w2; r.partial = partial;
+        int rc = launch_mlp_ring<kForward>(r, dim3(n_tb, p.r_vt), st);
+        if (rc != ARROL_OK) return rc;
+        arrol_launch(score_mlp_small_finish_kernel, dim3((n_rows + 255) / 256), dim3(256), 0, st, partial, p.r_vt,
+                     n_rows, b2, score, prob);
+        arrol_launch(mlp_residual_kernel, dim3(n_rblocks), dim3(1024), 0, st, score, prob, labels, n_rows, resid, bsum);
+        arrol_launch(mlp_residual_finish_kernel, dim3(1), dim3(1), 0, st, bsum, n_rblocks, n_rows, loss_out, grad_b2);
+        r.resid = resid; r.delta_t = dt; r.delta_stride = p.n_pad; r.unit_partial = unit;
+        rc = launch_mlp_ring<kDelta>(r, dim3(n_tb, p.r_vt), st);
+        if (rc != ARROL_OK) return rc;
+        arrol_launch(reduce_rows_f32_kernel<0>, dim3((m + 31) / 32), dim3(256), 0, st, unit, n_tb * 4,
+                     static_cast<int64_t>(2) * m, static_cast<int64_t>(m), 1.f, grad_w2);
+        arrol_launch(reduce_rows_f32_kernel<0>, dim3((m + 31) / 32), dim3(256), 0, st, unit + m, n_tb * 4,
+                     static_cast<int64_t>(2) * m, static_cast<int64_t>(m), 1.f, grad_b1);
+        arrol_launch(mlp_transpose_kernel, dim3(p.n_pad / 64, (d + 63) / 64), dim3(256), 0, st,
+                     static_cast<const uint16_t*>(hidden), row_stride_elems, row_index, n_rows, d, p.n_pad, ht);
+        float* rslab = reinterpret_cast<float*>(ws + p.off_rslab);
+        MlpRingArgs g = {};
+        g.a = dt; g.a_stride = static_cast<unsigned>(p.n_pad) * 2; g.a_rows = m;
+        g.b = ht; g.b_stride = static_cast<unsigned>(p.n_pad) * 2; g.b_rows = d;
+        g.n_k64 = p.n_kc; g.k64_per_split = p.r_k64_per_split;
+        g.c_out = p.r_splits > 1 ? rslab : grad_w1; g.c_stride = d;
+        rc = launch_mlp_ring<kWgrad>(g, dim3(p.r_cb, p.r_vt, p.r_splits), st);
+        if (rc != ARROL_OK) return rc;
+        if (p.r_splits > 1) {
+            const int64_t width = static_cast<int64_t>(m) * d;
+            arrol_launch(reduce_rows_f32_kernel<0>, dim3(static_cast<unsigned>((width + 31) / 32)), dim3(256), 0, st,
+                         rslab, p.r_splits, width, width, 1.f, grad_w1);
+        }
+        return arrol_launch_status();
+    }
     // forward pass, residuals and loss
     MlpArgs a = {};
     a.hidden = static_cast<const uint16_t*>(hidden); a.row_stride = row_stride_elems; a.row_index = row_index;
@@ -605,8 +838,8 @@ extern "C" int arrol_score_mlp_grad(const void* hidden, int64_t row_stride_elems
         rc = launch_mlp<kForward>(a, dim3(p.n_rb), st);
         if (rc != ARROL_OK) return rc;
     }
-    arrol_launch(mlp_residual_kernel, dim3(1), dim3(1024), 0, st, score, prob, labels, n_rows, resid, loss_out,
-                       grad_b2);
+    arrol_launch(mlp_residual_kernel, dim3(n_rblocks), dim3(1024), 0, st, score, prob, labels, n_rows, resid, bsum);
+    arrol_launch(mlp_residual_finish_kernel, dim3(1), dim3(1), 0, st, bsum, n_rblocks, n_rows, loss_out, grad_b2);
     // delta^T and the per-unit sums
     a.resid = resid; a.delta_t = dt; a.delta_stride = p.n_pad; a.unit_partial = unit;
     rc = launch_mlp<kDelta>(a, dim3(p.n_rb), st);

@@ -329,7 +329,8 @@ def test_whole_path_is_deterministic(A, W):
 
 # ------------------------------------------------------------------------------- MLP head
 @pytest.mark.parametrize("n,d,m", [(32, 256, 64), (1, 8, 1), (130, 264, 100), (512, 2048, 512), (300, 4096, 257),
-                                   (1000, 3072, 768)])
+                                   (1000, 3072, 768),
+                                   (4500, 128, 300), (4097, 64, 7), (6000, 1024, 513)])     # beyond 4,096 rows: the ring-pipeline kernel
 def test_score_mlp_matches_oracle(A, n, d, m):
     say("score_mlp n=%d d=%d m=%d" % (n, d, m))
     g = torch.Generator(device=DEV); g.manual_seed(n + d + m)

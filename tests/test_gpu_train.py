@@ -192,7 +192,8 @@ def check_mlp_grad(A, hidden, w1, b1, w2, b2, labels, row_index=None):
 
 
 @pytest.mark.parametrize("n,d,m", [(1, 8, 1), (32, 256, 64), (130, 264, 100), (300, 1024, 257), (512, 2048, 512),
-                                   (1500, 512, 300)])
+                                   (1500, 512, 300),
+                                   (4500, 128, 300), (4097, 64, 7), (5000, 192, 512)])     # beyond 4,096 rows: the ring-pipeline kernels
 def test_score_mlp_grad_matches_oracle(A, n, d, m):
     print("[case] score_mlp_grad n=%d d=%d m=%d" % (n, d, m), flush=True)
     hidden, w1, b1, w2, labels = mlp_case(n, d, m, seed=n + d + m)
