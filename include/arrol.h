@@ -73,7 +73,7 @@ int arrol_score(const void* hidden, int64_t row_stride_elems, const int64_t* row
                 float* score_out, float* prob_out, void* stream);
 
 /*
- * Stage 1, MLP head (Sec. 4.2: the quality head "can be a simple 2-layer MLP"; neither width nor
+ * Stage 1, MLP head (Sec. 4.2 allows a small two-layer MLP as the quality head; neither width nor
  * activation is given - ReLU is this build's reading):
  *   a = relu(W1 h + b1),  s_i = <w2, a> + b2,  q_i = sigmoid(s_i)
  * hidden, row_stride_elems, row_index, score_out, prob_out as in arrol_score.
@@ -119,7 +119,7 @@ typedef struct arrol_kv_layout {
 
 /*
  * Stage 3 -- compaction / re-batch (Sec. 4.3 (i): pruned requests leave the pool so their
- * capacity is reused; (ii) and Alg. 1 "Filter pruned rollouts, rebatch").
+ * capacity is reused; (ii) and the frontend step of Alg. 1 that drops the pruned rollouts and re-batches the rest).
  * Survivor rank r (r-th entry of survivor_idx, source rollout s) owns
  * np_r = min(ceil(seq_len_src[s] / page_tokens), max_pages_per_seq) destination pages
  * starting at base_r = sum_{r' < r} np_r'.  For every layer and K|V the source page
@@ -264,7 +264,8 @@ int arrol_calibrate(const int64_t* c_pos, const int64_t* c_neg, int32_t B, arrol
                     float* q_lut, float* p_lut, double* delta, void* stream);
 
 /*
- * Alg. 1 "Prune r_i w.p. 1 - p_i; record prune flag": p_i = p_lut[b(s_i)], rollout i survives iff
+ * Alg. 1, backend: a rollout that reaches the detection length is pruned with probability 1 - p_i and the
+ * decision recorded.  p_i = p_lut[b(s_i)], rollout i survives iff
  * uniforms[i] < p_i (fp32 comparison; the caller supplies the random numbers).
  * s_norm, uniforms fp32 [N]; p_lut fp32 [B]; p_out NULL or fp32 [N]; keep_mask uint8 [N];
  * survivor_idx int32 [N]: the survivors' ids ascending, then -1 up to N (so it can be handed to
@@ -306,7 +307,7 @@ int arrol_trace_confidence(const float* conf, const int64_t* cu_seqlens, int64_t
                            double* bottom_out, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * ---- GRPO on the survivors (Sec. 3 "Group-Relative Policy Optimization"; Alg. 1 "advantages") -------------
+ * ---- GRPO on the survivors (Sec. 3 "Group-Relative Policy Optimization"; Alg. 1, advantage step) -------------
  * Group-relative advantage  A_i = (R_i - mean(R_group)) / (std(R_group) + eps)  over the rollouts of one prompt
  * that survived pruning; rollouts of group g are [group_offsets[g], group_offsets[g+1]) (int64 [n_groups+1],
  * clamped into [0, N]).  std^2 = sum (R - mean)^2 / (n - ddof), ddof 0 (population) or 1; std = 0 when
@@ -338,7 +339,7 @@ int arrol_grpo_objective(const float* logp, const float* logp_ref, const int64_t
                          int64_t* n_clipped, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * ---- Training the quality head (Sec. 4.2; Sec. 4.3 (iii); Alg. 1 "optimizer step on policy and quality head") ----
+ * ---- Training the quality head (Sec. 4.2; Sec. 4.3 (iii); Alg. 1, the frontend's optimizer step) ----
  * The head is fitted on the fly to the rollouts' final rewards with a cross-entropy loss; the hidden states
  * are constants (no gradient reaches the backbone).  For the linear head, with q_i = sigmoid(<w,h_i> + bias):
  *   L = -(1/N) sum_i [ y_i log q_i + (1-y_i) log(1-q_i) ]

@@ -141,7 +141,7 @@ def compact(kv_src, block_table_src, seq_len_src, tokens_src, survivor_idx,
     """Gather the survivors' paged KV cache and token buffers into a dense pool.
 
     Sec. 4.3 (i): pruned requests leave the pool at once so their capacity is
-    reused; (ii) / Alg. 1 "Filter pruned rollouts, rebatch": survivors are
+    reused; (ii) / Alg. 1's frontend step that drops pruned rollouts: survivors are
     re-batched.  The paper fixes no layout; this build's contract is:
 
     kv_src          [L, 2, P_src, page_tokens, H_kv, hd] uint16 (bf16 bits)
@@ -197,7 +197,7 @@ def logprob(hidden_bits, lm_head_bits, targets):
     """Per-token log-probability of the sampled token under the policy,
     log pi_theta(o_t | o_<t): the quantity inside GRPO's importance ratio
     (Sec. 3) that the frontend computes on the re-batched survivors (Sec. 4.3
-    (ii); Alg. 1 "Compute rewards, log-probs").  Temperature 1, no LM-head
+    (ii); Alg. 1's frontend step for rewards and log-probs).  Temperature 1, no LM-head
     bias; row t of `hidden` is already aligned with targets[t].
 
     hidden_bits [T, d] uint16, lm_head_bits [V, d] uint16, targets [T] int.
@@ -402,7 +402,7 @@ def compact_inplace(kv, block_table_src, seq_len_src, survivor_idx):
 # 2-layer MLP quality head
 # ----------------------------------------------------------------------------
 def score_mlp(hidden_bits, w1_bits, b1, w2, b2=0.0):
-    """Quality head as a 2-layer MLP (Sec. 4.2: the head "can be a simple 2-layer MLP") followed by the
+    """Quality head as a 2-layer MLP (Sec. 4.2 allows a small two-layer MLP as the head) followed by the
     sigmoid normalisation of App. A.4.  Reading (the paper gives neither width nor activation):
         a = relu(W1 h + b1),  s = <w2, a> + b2,  q = sigmoid(s)
     hidden_bits [N, d] uint16 (bf16), w1_bits [m, d] uint16 (bf16), b1 [m] fp32, w2 [m] fp32.
@@ -470,7 +470,7 @@ def score_ce_grad(hidden_bits, w, bias, labels):
 
 
 def adamw_step(param, grad, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0):
-    """One AdamW update (Alg. 1 asks for an "optimizer step" on the quality head and names no optimizer;
+    """One AdamW update (Alg. 1 updates the quality head in its optimizer step and names no optimizer;
     AdamW with decoupled weight decay, Loshchilov & Hutter 2019, is this build's reading):
         m <- b1 m + (1-b1) g;  v <- b2 v + (1-b2) g^2
         p <- p - lr * ( (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps) + wd * p )

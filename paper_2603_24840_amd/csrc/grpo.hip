@@ -1,5 +1,5 @@
-// GRPO on the surviving rollouts (Sec. 3 "Group-Relative Policy Optimization"; Alg. 1 "Compute rewards,
-// log-probs, advantages"): the group-relative advantage and the clipped-ratio objective with its derivative
+// GRPO on the surviving rollouts (Sec. 3 "Group-Relative Policy Optimization"; the frontend step of Alg. 1
+// that follows the log-probs): the group-relative advantage and the clipped-ratio objective with its derivative
 // with respect to the per-token log-probabilities that arrol_logprob produces.  A few bytes per token and a
 // handful of groups: latency-bound kernels, written for fixed summation order and fp64 decisions rather than
 // for bandwidth.

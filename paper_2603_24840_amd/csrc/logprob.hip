@@ -72,7 +72,7 @@ struct LaneState {
 // Folds one finished accumulator tile into the running (max, sumexp, target logit) and clears it.
 // acc[i][j][v] is the logit of vocab row vrow0 + i*32 + (v/4)*8 + lh*4 + v%4 for the lane's token of
 // block j (MFMA 32x32 result layout); WROWS = vocab rows per wave tile.
-template <int TM, int TN, int WROWS>
+template <int TM, int TN, int WROWS, bool CLEAR = true>
 __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[TM][TN], LaneState<TN>& st, int vrow0, int V, int lh) {
     if (vrow0 + WROWS > V) {  // tile hangs over the end of the vocabulary
 #pragma unroll
@@ -109,7 +109,7 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[TM][TN], LaneState<T
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 sum += __builtin_amdgcn_exp2f(fmaf(acc[i][j][v], kLog2e, neg));
-                acc[i][j][v] = 0.f;
+                if (CLEAR) acc[i][j][v] = 0.f;
             }
         // difference first: exactly 0 when the maximum did not move (also for the -1e30 sentinel)
         st.run_s[j] = st.run_s[j] * __builtin_amdgcn_exp2f((st.run_m[j] - m_new) * kLog2e) + sum;
@@ -307,6 +307,12 @@ __global__ __launch_bounds__(C::NT) void logprob_kernel(LogprobArgs a) {
 //               matrix pipe never waits for an LDS round trip behind a barrier.
 // The barrier inside iteration i certifies the W part of slot i+2 and the H part of slot i+1 and
 // releases slot i-1 (W lines) / slot i-2.. for refilling; see the table in the loop for who loads what.
+// The first K16 step of every vocabulary tile takes the constant 0 as its MFMA addend, so the epilogue
+// never clears the accumulators.
+// (ring_nt.h holds the same pipeline in a general form - row strides, K ranges, an epilogue callback - for
+// the MLP head's kernels, which walk one tile per workgroup.  This kernel walks many tiles with the epilogue
+// between them and keeps its own instance: built on the general form it ran 7 % slower, the compiler then
+// spilling scalar registers inside the loop.)
 // ---------------------------------------------------------------------------------------------
 template <int BM_, int BN_, int WM_, int WN_>
 struct RingTile {
@@ -344,9 +350,6 @@ __global__ __launch_bounds__(C::NT) void logprob_ring_kernel(LogprobArgs a) {
     const int l31 = lane & 31, lh = lane >> 5;
     const int64_t tok0 = static_cast<int64_t>(tb) * BN;
     const int n_k64 = a.d / 64;
-    // (readfirstlane: wave-uniform by construction; it keeps the loop control in scalar registers)
-    const int n_pairs = __builtin_amdgcn_readfirstlane((vt_hi - vt_lo) * n_k64);   // pair = two K32 slots = one 128-byte line per row
-    const int n_chunks = 2 * n_pairs;
 
     // ---- loader geometry: one instruction moves 16 rows x 64 bytes; lane -> (row lane/4, physical
     //      16-byte position lane%4), which holds logical chunk (lane%4) ^ ((row/4)%4) -----------
@@ -377,9 +380,12 @@ __global__ __launch_bounds__(C::NT) void logprob_ring_kernel(LogprobArgs a) {
             a_voff[g] = static_cast<unsigned>(r * row_bytes + ld_kb);
         }
     };
-    // two load streams, each walking the pairs 0 .. n_pairs-1: W lines (A) and H lines (B)
-    int a_vt = vt_lo, a_k64 = 0, a_slot = 0, a_issued = 0;
-    int b_k64 = 0, b_slot = 0, b_issued = 0;
+    // two load streams, each walking the pairs (pair = two K32 slots = one 128-byte line per row) of the
+    // workgroup's vocabulary range: W lines (A) and H lines (B).  Past the last pair both keep requesting lines
+    // that exist (W: the last line again; H: its tile from the start) into ring slots nobody reads any more,
+    // so the loop below needs no variant without loads.
+    int a_vt = vt_lo, a_k64 = 0, a_slot = 0;
+    int b_k64 = 0, b_slot = 0;
     const char* a_base = reinterpret_cast<const char*>(a.W) + a_vt * tile_bytes;
     const char* b_base = reinterpret_cast<const char*>(a.H) + tok0 * row_bytes;
     point_at_tile(a_vt);
@@ -405,17 +411,21 @@ __global__ __launch_bounds__(C::NT) void logprob_ring_kernel(LogprobArgs a) {
             b_base += 128;
             if (++b_k64 == n_k64) { b_k64 = 0; b_base -= row_bytes; }   // next vocabulary tile: H rewinds
             b_slot = b_slot + 2 >= RING ? b_slot + 2 - RING : b_slot + 2;
-            ++b_issued;
         } else {
-            a_base += 128;
-            if (++a_k64 == n_k64) {   // next vocabulary tile: W moves on by a tile minus the row just walked
-                a_k64 = 0;
-                ++a_vt;
-                a_base += tile_bytes - row_bytes;
-                point_at_tile(a_vt);
+            if (a_vt < vt_hi) {
+                a_base += 128;
+                if (++a_k64 == n_k64) {   // next vocabulary tile: W moves on by a tile minus the row just walked
+                    a_k64 = 0;
+                    ++a_vt;
+                    if (a_vt < vt_hi) {
+                        a_base += tile_bytes - row_bytes;
+                        point_at_tile(a_vt);
+                    } else {
+                        a_base -= 128;   // past the last pair: keep requesting the last line (nobody reads that slot any more)
+                    }
+                }
             }
             a_slot = a_slot + 2 >= RING ? a_slot + 2 - RING : a_slot + 2;
-            ++a_issued;
         }
     };
     auto issue_group = [&](auto stream) {
@@ -457,6 +467,11 @@ __global__ __launch_bounds__(C::NT) void logprob_ring_kernel(LogprobArgs a) {
     auto mma = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], int x) {
         acc[x / TN][x % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[x / TN], fb[x % TN], acc[x / TN][x % TN], 0, 0, 0);
     };
+    // first K16 step of a tile: the addend is the constant 0, so the accumulators never have to be cleared
+    auto mma0 = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], int x) {
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        acc[x / TN][x % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[x / TN], fb[x % TN], zero, 0, 0, 0);
+    };
 
     // Load schedule (pair p = chunks 2p, 2p+1 -> slots 2p % RING, (2p+1) % RING):
     //   up front           A(0), B(0), A(1)
@@ -464,54 +479,49 @@ __global__ __launch_bounds__(C::NT) void logprob_ring_kernel(LogprobArgs a) {
     //   iteration 2p-3     A(p)   (odd iterations,  p >= 2)
     // The barrier inside iteration i needs every group requested before iteration i to have landed
     // (W part of slot i+2, H part of slot i+1), i.e. only this iteration's own loads may be in flight.
-    if (n_pairs > 0) { issue_group(kA); issue_group(kB); }
-    if (n_pairs > 1) issue_group(kA);
-    if (n_pairs > 0) {
-        if (n_pairs > 1) wait_vmcnt<C::LOADS>(); else wait_vmcnt<0>();
-        __syncthreads();
+    issue_group(kA); issue_group(kB); issue_group(kA);
+    wait_vmcnt<C::LOADS>();
+    __syncthreads();
 #pragma unroll
-        for (int j = 0; j < TN; ++j) read_b(fb0, lds, b_off0, j);
+    for (int j = 0; j < TN; ++j) read_b(fb0, lds, b_off0, j);
 #pragma unroll
-        for (int m = 0; m < TM; ++m) read_a(fa0, lds, a_off0, m);
-    }
-    int vt = vt_lo, kc = 0, slot = 0;
-    const int n_kc = 2 * n_k64;
-    // `always` = std::true_type: steady state, the iteration's four loads are unconditional (no branches
-    // between the MFMAs); std::false_type: drain, loads only while the stream still has pairs to request.
-    auto iteration = [&](auto stream, auto always) {
-        constexpr bool is_b = decltype(stream)::value;
+    for (int m = 0; m < TM; ++m) read_a(fa0, lds, a_off0, m);
+    int slot = 0;
+    // `first` = std::true_type: first K32 chunk of a vocabulary tile (its first K16 step starts the accumulators from 0)
+    auto iteration = [&](auto stream, auto first) {
+        constexpr bool is_first = decltype(first)::value;
         const unsigned char* cur = lds + slot * C::SLOT_BYTES;
         slot = slot + 1 == RING ? 0 : slot + 1;
         const unsigned char* nxt = lds + slot * C::SLOT_BYTES;
-        const bool loads = decltype(always)::value || (is_b ? b_issued : a_issued) < n_pairs;   // wave-uniform
+        auto m0 = [&](int x) { if constexpr (is_first) mma0(fa0, fb0, x); else mma(fa0, fb0, x); };
         // ---- K16 step 0 -------------------------------------------------------------------------
-        mma(fa0, fb0, 0); mma(fa0, fb0, 1);
+        m0(0); m0(1);
         __builtin_amdgcn_sched_barrier(0);
         read_b(fb1, cur, b_off1, 0); read_b(fb1, cur, b_off1, 1);
-        if (loads) issue_one(stream, 0);
+        issue_one(stream, 0);
         __builtin_amdgcn_sched_barrier(0);
-        mma(fa0, fb0, 2); mma(fa0, fb0, 3);
+        m0(2); m0(3);
         __builtin_amdgcn_sched_barrier(0);
         read_a(fa1, cur, a_off1, 0); read_a(fa1, cur, a_off1, 1);
         __builtin_amdgcn_sched_barrier(0);
-        mma(fa0, fb0, 4); mma(fa0, fb0, 5);
+        m0(4); m0(5);
         __builtin_amdgcn_sched_barrier(0);
         read_a(fa1, cur, a_off1, 2); read_a(fa1, cur, a_off1, 3);
-        if (loads) issue_one(stream, 1);
+        issue_one(stream, 1);
         __builtin_amdgcn_sched_barrier(0);
-        mma(fa0, fb0, 6); mma(fa0, fb0, 7);
+        m0(6); m0(7);
         __builtin_amdgcn_sched_barrier(0);
         // ---- K16 step 1 -------------------------------------------------------------------------
         mma(fa1, fb1, 0); mma(fa1, fb1, 1);
         __builtin_amdgcn_sched_barrier(0);
         read_a(fa0, nxt, a_off0, 0); read_a(fa0, nxt, a_off0, 1);           // W part of slot i+1: certified already
-        if (loads) issue_one(stream, 2);
+        issue_one(stream, 2);
         __builtin_amdgcn_sched_barrier(0);
         mma(fa1, fb1, 2); mma(fa1, fb1, 3);
         __builtin_amdgcn_sched_barrier(0);
         // everything this wave requested before this iteration has landed (3 younger loads may fly);
         // its own LDS reads are complete; then all waves agree
-        if (loads) wait_vmcnt<3>(); else wait_vmcnt<0>();
+        wait_vmcnt<3>();
         __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0) only
         __syncthreads();
         read_b(fb0, nxt, b_off0, 0); read_b(fb0, nxt, b_off0, 1);           // H part of slot i+1: certified just now
@@ -519,29 +529,20 @@ __global__ __launch_bounds__(C::NT) void logprob_ring_kernel(LogprobArgs a) {
         __builtin_amdgcn_sched_barrier(0);
         mma(fa1, fb1, 4); mma(fa1, fb1, 5);
         __builtin_amdgcn_sched_barrier(0);
-        if (loads) { issue_one(stream, 3); advance(stream); }
+        issue_one(stream, 3); advance(stream);
         __builtin_amdgcn_sched_barrier(0);
         mma(fa1, fb1, 6); mma(fa1, fb1, 7);
     };
-    auto end_of_pair = [&]() {
-        kc += 2;
-        if (kc == n_kc) {   // a tile ends on an odd chunk (d is a multiple of 64)
-            tile_epilogue<TM, TN, BM / C::WM>(acc, st, vt * BM + wm * (BM / C::WM), a.V, lh);
-            kc = 0;
-            ++vt;
-        }
-    };
-    // even iteration i requests the H lines of pair i/2 + 1, odd iteration i+1 the W lines of pair i/2 + 2
-    int i = 0;
-    for (; i < n_chunks && a_issued < n_pairs; i += 2) {   // steady state (the W stream runs one pair ahead)
+    // even iteration i requests the H lines of pair i/2 + 1, odd iteration i+1 the W lines of pair i/2 + 2; past the
+    // last pair both streams keep requesting lines that exist, into slots nobody reads, so there is no drain variant
+    for (int vt = vt_lo; vt < vt_hi; ++vt) {
         iteration(kB, std::true_type{});
-        iteration(kA, std::true_type{});
-        end_of_pair();
-    }
-    for (; i < n_chunks; i += 2) {                          // drain: the last two pairs
-        iteration(kB, std::false_type{});
         iteration(kA, std::false_type{});
-        end_of_pair();
+        for (int k = 1; k < n_k64; ++k) {
+            iteration(kB, std::false_type{});
+            iteration(kA, std::false_type{});
+        }
+        tile_epilogue<TM, TN, BM / C::WM, false>(acc, st, vt * BM + wm * (BM / C::WM), a.V, lh);
     }
     wait_vmcnt<0>();
     __builtin_amdgcn_s_waitcnt(0xC07F);

@@ -1,5 +1,5 @@
-// arrol_score_mlp: quality head as a 2-layer MLP (Sec. 4.2: the rollout quality head "can be a simple
-// 2-layer MLP"), followed by the sigmoid normalisation (App. A.4):
+// arrol_score_mlp: quality head as a 2-layer MLP (Sec. 4.2 allows a small two-layer MLP as the
+// rollout quality head), followed by the sigmoid normalisation (App. A.4):
 //     a = relu(W1 h + b1),  s = <w2, a> + b2,  q = sigmoid(s)
 // One fused kernel: bf16 MFMA for W1 h (transposed, A^T = W1 H^T, so that a lane's accumulator values
 // belong to one rollout and the reduction over hidden units is lane-local), bias + ReLU + the dot with w2

@@ -1,4 +1,4 @@
-// Training of the quality head (Sec. 4.2, Sec. 4.3 (iii), Alg. 1 "optimizer step on ... quality head"):
+// Training of the quality head (Sec. 4.2, Sec. 4.3 (iii), the optimizer step at the end of Alg. 1's frontend loop):
 // cross-entropy loss of the linear head against the rollouts' rewards with its gradient, and an AdamW update.
 // The hidden states are constants (the gradient stops at the backbone), so the gradient is one pass over the
 // [N, d] matrix: HBM-streaming, every row read once and kept in registers between the forward dot product and
