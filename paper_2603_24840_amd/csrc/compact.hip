@@ -362,20 +362,32 @@ __global__ __launch_bounds__(kPlanThreads) void inplace_fused_plan_kernel(
     }
 }
 
-// pair k of the mover -> hole list, every (layer, K|V) slab: workgroup (slab, k) with k < m_bound, the
-// host-side bound on the pair count; the pairs beyond the device-side count exit at once.  Slab by slab
-// and, inside a slab, in ascending page order (both lists ascend).  Measured on the 8.6 GB pool against
-// the alternatives: numbering only the m * n_slabs real copies (no idle workgroups between slabs) -7 %,
-// neighbours on different slabs -3 %, a scrambled pair order -3 %, groups of 8 or 64 pairs per slab visit
-// -10 %.
+// pair k of the mover -> hole list, every (layer, K|V) slab: one workgroup per (slab, k), k below the
+// host-side bound on the pair count; pairs beyond the device-side count exit at once.  Both lists ascend.
+// The order in which the grid visits (slab, k) is chosen on the host from measurements of the pool sizes of
+// the benchmark configurations: slab by slab (group == 0) is fastest for 16 KiB chunks (5.16 TB/s on the
+// 8.6 GB pool against 4.7 for the grouped order), `group` = 16 consecutive pairs per slab visit, all slabs
+// before the next 16 pairs, for 32 KiB chunks (5.88 TB/s on the 155 GB pool and 5.65 on the 120 GB one
+// against 5.39 slab by slab).  Numbering only the m * n_slabs real copies (no idle workgroups in between),
+// neighbours on different slabs and a scrambled pair order all measured slower than both.
 __global__ __launch_bounds__(kCopyThreads) void inplace_copy_pairs_kernel(
     u32x4* __restrict__ kv, int64_t chunk_vec, int64_t P, const int32_t* __restrict__ hole_list,
-    const int32_t* __restrict__ mover_list, const int32_t* __restrict__ counters, int64_t m_bound) {
-    const int64_t bid = blockIdx.x;
-    const int64_t slab = bid / m_bound, k = bid - slab * m_bound;
-    if (k >= counters[1]) return;
-    const u32x4* s = kv + (slab * P + mover_list[k]) * chunk_vec;
-    u32x4* d = kv + (slab * P + hole_list[k]) * chunk_vec;
+    const int32_t* __restrict__ mover_list, const int32_t* __restrict__ counters, unsigned m_bound, unsigned group) {
+    const unsigned bid = blockIdx.x;
+    unsigned slab, k;
+    if (group == 0) {
+        slab = bid / m_bound;
+        k = bid - slab * m_bound;
+    } else {
+        const unsigned n_slabs = gridDim.x / m_bound;
+        const unsigned per_group = n_slabs * group;
+        const unsigned grp = bid / per_group, rem = bid - grp * per_group;
+        slab = rem / group;
+        k = grp * group + (rem - slab * group);     // the host rounds m_bound up to whole groups
+    }
+    if (static_cast<int>(k) >= counters[1]) return;
+    const u32x4* s = kv + (static_cast<int64_t>(slab) * P + mover_list[k]) * chunk_vec;
+    u32x4* d = kv + (static_cast<int64_t>(slab) * P + hole_list[k]) * chunk_vec;
     for (int64_t v0 = 0; v0 < chunk_vec; v0 += kCopyThreads * kCopyUnroll) {
         u32x4 x[kCopyUnroll];
 #pragma unroll
@@ -567,11 +579,14 @@ extern "C" int arrol_compact_inplace(void* kv, arrol_kv_layout layout, const int
         // no more pairs than survivor pages, than dead pages (P - live >= holes), or than half the pool
         int64_t m_bound = slots < P / 2 ? slots : P / 2;
         const int n_slabs = layout.n_layers * 2;
+        const unsigned group = chunk_bytes >= 32768 ? 16u : 0u;   // see inplace_copy_pairs_kernel
+        if (group) m_bound = (m_bound + group - 1) / group * group;
         const int64_t blocks = m_bound * n_slabs;
         if (blocks > INT32_MAX) return ARROL_EINVAL;
         if (blocks > 0)
             arrol_launch(inplace_copy_pairs_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kCopyThreads), 0, st,
-                         static_cast<u32x4*>(kv), chunk_bytes / 16, P, hole_list, mover_list, counters, m_bound);
+                         static_cast<u32x4*>(kv), chunk_bytes / 16, P, hole_list, mover_list, counters,
+                         static_cast<unsigned>(m_bound), group);
         return arrol_launch_status();
     }
     if (P > 0) {
