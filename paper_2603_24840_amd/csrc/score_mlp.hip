@@ -41,7 +41,7 @@ constexpr int kPassB = BR * (BK / 8) / kThreads;
 
 __device__ __forceinline__ int chunk_offset(int r, int c) { return r * 128 + ((c ^ ((r >> 1) & 7)) << 4); }
 
-enum MlpMode { kForward = 0, kDelta = 1, kWgrad = 2 };
+enum MlpMode { kForward = 0, kDelta = 1, kWgrad = 2, kForwardKeep = 3 };   // kForwardKeep: ring kernel only
 
 // The tile loop multiplies A rows (w1, a_stride elements apart, m of them) with B rows (hidden, n_rows of
 // them) over a contiguous K extent of d elements.
@@ -419,8 +419,9 @@ __global__ __launch_bounds__(256) void score_mlp_small_finish_kernel(const float
 // accumulator tile per workgroup: grid = (blocks of 256 B rows, tiles of 256 A rows, K splits).
 //   forward  A = W1 [m, d], B = hidden [N, d]: bias + ReLU + w2 dot per rollout (lane-local over the
 //            units), partial scores [unit tile][rollout] to the workspace, summed by the finish kernel;
-//   delta    same product; delta^T (bf16, unit-major) and the per-unit sums over each wavefront's 64 rollouts
-//            to unit_partial[(block * 4 + wave column)][2][m];
+//            for the gradient call the same pass also keeps the activations a = relu(pre) in fp32, unit-major
+//            (the accumulator's own layout: 32 lanes = 32 consecutive rollouts), so that nothing is recomputed:
+//            delta^T = r w2 [a > 0] and the per-unit sums are then one streaming pass (mlp_delta_kernel);
 //   wgrad    A = delta^T [m, n_pad], B = H^T [d, n_pad] over K = rollouts (split): fp32 tile stores.
 using RingCfg = ring_nt::RingTile<256, 256, 2, 4>;
 
@@ -430,8 +431,7 @@ struct MlpRingArgs {
     int a_rows, b_rows, n_k64, k64_per_split;
     const float* b1; const float* w2;
     float* partial;              // forward: [gridDim.y][b_rows]
-    const float* resid;          // delta: [b_rows]
-    uint16_t* delta_t; int64_t delta_stride; float* unit_partial;   // delta^T has delta_stride columns (zero beyond b_rows)
+    float* act_t; int64_t act_stride;       // forward for the gradient: relu(pre), [a_rows][act_stride] fp32
     float* c_out; int64_t c_stride;         // wgrad: [gridDim.z][a_rows][c_stride]
 };
 
@@ -461,14 +461,6 @@ __global__ __launch_bounds__(RingCfg::NT) void mlp_ring_kernel(MlpRingArgs a) {
     const int unit0 = vt * BM + wm * (BM / C::WM);           // first A row of this wavefront
     const int row0 = tb * BN + wn * (BN / C::WN);            // first B row of this wavefront
     float part[TN] = {0.f, 0.f};
-    float resid[TN] = {0.f, 0.f};
-    if (MODE == kDelta) {
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int r = row0 + j * 32 + l31;
-            resid[j] = r < a.b_rows ? a.resid[r] : 0.f;
-        }
-    }
     f32x16 acc[TM][TN];
     ring_nt::walk<C>(w, lds, acc, [](f32x16 (&)[TM][TN], int) {});   // one tile: the epilogue runs here, after the walk
     {
@@ -490,40 +482,21 @@ __global__ __launch_bounds__(RingCfg::NT) void mlp_ring_kernel(MlpRingArgs a) {
                 } else {
                     const float bias = (live && a.b1) ? a.b1[u] : 0.f;
                     const float wu = live ? a.w2[u] : 0.f;
-                    if (MODE == kForward) {
+                    float* arow = MODE == kForwardKeep ? a.act_t + static_cast<int64_t>(live ? u : 0) * a.act_stride : nullptr;
 #pragma unroll
-                        for (int j = 0; j < TN; ++j) {
-                            part[j] = fmaf(fmaxf(acc[i][j][v] + bias, 0.f), wu, part[j]);
-                            acc[i][j][v] = 0.f;
+                    for (int j = 0; j < TN; ++j) {
+                        const float act = fmaxf(acc[i][j][v] + bias, 0.f);
+                        part[j] = fmaf(act, wu, part[j]);
+                        if (MODE == kForwardKeep) {
+                            const int col = row0 + j * 32 + l31;
+                            if (live && col < a.b_rows) arow[col] = act;
                         }
-                    } else {
-                        float gw = 0.f, gb = 0.f;
-                        uint16_t* drow = a.delta_t + static_cast<int64_t>(live ? u : 0) * a.delta_stride + row0 + l31;
-#pragma unroll
-                        for (int j = 0; j < TN; ++j) {
-                            const float pre = acc[i][j][v] + bias;
-                            const float dl = pre > 0.f ? resid[j] * wu : 0.f;
-                            gw = fmaf(resid[j], fmaxf(pre, 0.f), gw);
-                            gb += dl;
-                            if (live && row0 + j * 32 + l31 < a.delta_stride) drow[j * 32] = f32_to_bf16_rne(dl);   // 0 in the padding
-                            acc[i][j][v] = 0.f;
-                        }
-                        // sum over the 32 rollout lanes of this half-wave (both halves run the same steps)
-#pragma unroll
-                        for (int msk = 16; msk >= 1; msk >>= 1) {
-                            gw += __shfl_xor(gw, msk, ARROL_WAVE);
-                            gb += __shfl_xor(gb, msk, ARROL_WAVE);
-                        }
-                        if (live && l31 == 0) {
-                            float* up = a.unit_partial + static_cast<int64_t>(tb * C::WN + wn) * 2 * a.a_rows;
-                            up[u] = gw;
-                            up[a.a_rows + u] = gb;
-                        }
+                        acc[i][j][v] = 0.f;
                     }
                 }
             }
     }
-    if (MODE != kForward) return;
+    if (MODE == kWgrad) return;
     // the two lane halves and the two wavefront rows hold different units of the same rollouts
     float* red = reinterpret_cast<float*>(lds);   // [WM][BN]
 #pragma unroll
@@ -590,6 +563,61 @@ __global__ void mlp_residual_finish_kernel(const float* __restrict__ block_sums,
     if (grad_b2) *grad_b2 = b;
 }
 
+// delta^T and the per-unit sums from the kept activations: one workgroup per unit u streams its row
+//   delta^T[u][i] = r_i w2_u [a_ui > 0] (bf16, 0 for n_rows <= i < n_pad),
+//   dL/dw2_u = sum_i r_i a_ui,  dL/db1_u = sum_i r_i w2_u [a_ui > 0],
+// each lane over its own columns in ascending order, then lanes, then wavefronts: a fixed summation order.
+constexpr int kDeltaThreads = 1024;
+__global__ __launch_bounds__(kDeltaThreads) void mlp_delta_kernel(const float* __restrict__ act_t, int64_t act_stride,
+                                                                  const float* __restrict__ resid,
+                                                                  const float* __restrict__ w2, int n_rows, int n_pad,
+                                                                  uint16_t* __restrict__ delta_t,
+                                                                  float* __restrict__ grad_w2,
+                                                                  float* __restrict__ grad_b1) {
+    __shared__ float red[2][kDeltaThreads / ARROL_WAVE];
+    const int u = blockIdx.x;
+    const float wu = w2[u];
+    const float* arow = act_t + static_cast<int64_t>(u) * act_stride;
+    uint16_t* drow = delta_t + static_cast<int64_t>(u) * n_pad;
+    float gw = 0.f, gb = 0.f;
+    for (int i = threadIdx.x * 4; i < n_pad; i += kDeltaThreads * 4) {   // n_pad is a multiple of 4
+        float av[4] = {0.f, 0.f, 0.f, 0.f}, rv[4] = {0.f, 0.f, 0.f, 0.f};
+        if (i + 3 < n_rows) {
+            const float4 a4 = *reinterpret_cast<const float4*>(arow + i);
+            const float4 r4 = *reinterpret_cast<const float4*>(resid + i);
+            av[0] = a4.x; av[1] = a4.y; av[2] = a4.z; av[3] = a4.w;
+            rv[0] = r4.x; rv[1] = r4.y; rv[2] = r4.z; rv[3] = r4.w;
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (i + q < n_rows) { av[q] = arow[i + q]; rv[q] = resid[i + q]; }
+        }
+        uint16_t dq[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float dl = av[q] > 0.f ? rv[q] * wu : 0.f;
+            gw = fmaf(rv[q], av[q], gw);
+            gb += dl;
+            dq[q] = f32_to_bf16_rne(dl);
+        }
+        uint2 o;
+        o.x = static_cast<uint32_t>(dq[0]) | (static_cast<uint32_t>(dq[1]) << 16);
+        o.y = static_cast<uint32_t>(dq[2]) | (static_cast<uint32_t>(dq[3]) << 16);
+        *reinterpret_cast<uint2*>(drow + i) = o;
+    }
+    gw = wave_sum_f32(gw);
+    gb = wave_sum_f32(gb);
+    const int lane = threadIdx.x & (ARROL_WAVE - 1), wave = threadIdx.x / ARROL_WAVE;
+    if (lane == 0) { red[0][wave] = gw; red[1][wave] = gb; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float a = 0.f, b = 0.f;
+        for (int w = 0; w < kDeltaThreads / ARROL_WAVE; ++w) { a += red[0][w]; b += red[1][w]; }
+        grad_w2[u] = a;
+        grad_b1[u] = b;
+    }
+}
+
 // out[c][i] = hidden[row(i)][c] for i < n_rows, 0 for n_rows <= i < n_pad: 64 x 64 tiles through LDS, 16 bytes
 // per lane on both sides (8 lanes cover the 128 bytes a tile row has in the source and in the destination)
 __global__ __launch_bounds__(256) void mlp_transpose_kernel(const uint16_t* __restrict__ hidden, int64_t row_stride,
@@ -626,7 +654,7 @@ __global__ __launch_bounds__(256) void mlp_transpose_kernel(const uint16_t* __re
 struct GradPlan {
     int n_rb, n_pad, n_cb, n_groups, n_kc, splits, kc_per_split;
     int r_cb, r_vt, r_splits, r_k64_per_split;
-    size_t off_score, off_prob, off_resid, off_bsum, off_ht, off_dt, off_unit, off_slab, off_small, off_rslab, total;
+    size_t off_score, off_prob, off_resid, off_bsum, off_ht, off_dt, off_unit, off_slab, off_small, off_rslab, off_act, total;
 };
 
 size_t align256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
@@ -652,9 +680,8 @@ GradPlan make_grad_plan(int n_rows, int d, int m) {
     p.off_bsum = o;  o = align256(o + sizeof(float) * 2 * ((n_rows + 1023) / 1024));
     p.off_ht = o;    o = align256(o + sizeof(uint16_t) * static_cast<size_t>(d) * p.n_pad);
     p.off_dt = o;    o = align256(o + sizeof(uint16_t) * static_cast<size_t>(m) * p.n_pad);
-    // per-unit partial sums: one row per 128 rollouts (tile kernel) or per 64 (ring kernel's wavefront columns)
-    const int unit_rows = p.n_rb > 4 * ((n_rows + 255) / 256) ? p.n_rb : 4 * ((n_rows + 255) / 256);
-    p.off_unit = o;  o = align256(o + sizeof(float) * static_cast<size_t>(unit_rows) * 2 * m);
+    // per-unit partial sums of the tile kernel: one row per 128 rollouts
+    p.off_unit = o;  o = align256(o + sizeof(float) * static_cast<size_t>(p.n_rb) * 2 * m);
     p.off_slab = o;
     if (p.splits > 1) o = align256(o + sizeof(float) * static_cast<size_t>(p.splits) * m * d);
     p.off_small = o;                      // partial scores of the small-batch / ring forward pass
@@ -673,6 +700,8 @@ GradPlan make_grad_plan(int n_rows, int d, int m) {
     p.r_splits = (p.n_kc + p.r_k64_per_split - 1) / p.r_k64_per_split;
     p.off_rslab = o;
     if (n_rows > kSmallMaxRows && d % 64 == 0 && p.r_splits > 1) o = align256(o + sizeof(float) * static_cast<size_t>(p.r_splits) * m * d);
+    p.off_act = o;                        // ring forward pass: kept activations, fp32 [m][n_pad]
+    if (n_rows > kSmallMaxRows && d % 64 == 0) o = align256(o + sizeof(float) * static_cast<size_t>(m) * p.n_pad);
     p.total = o;
     return p;
 }
@@ -790,19 +819,16 @@ extern "C" int arrol_score_mlp_grad(const void* hidden, int64_t row_stride_elems
         r.a = static_cast<const uint16_t*>(w1); r.a_stride = static_cast<unsigned>(d) * 2; r.a_rows = m;
         r.b = static_cast<const uint16_t*>(hidden); r.b_stride = static_cast<unsigned>(row_stride_elems * 2); r.b_rows = n_rows;
         r.n_k64 = d / 64; r.b1 = b1; r.w2 = w2; r.partial = partial;
-        int rc = launch_mlp_ring<kForward>(r, dim3(n_tb, p.r_vt), st);
+        float* act = reinterpret_cast<float*>(ws + p.off_act);
+        r.act_t = act; r.act_stride = p.n_pad;
+        int rc = launch_mlp_ring<kForwardKeep>(r, dim3(n_tb, p.r_vt), st);
         if (rc != ARROL_OK) return rc;
         arrol_launch(score_mlp_small_finish_kernel, dim3((n_rows + 255) / 256), dim3(256), 0, st, partial, p.r_vt,
                      n_rows, b2, score, prob);
         arrol_launch(mlp_residual_kernel, dim3(n_rblocks), dim3(1024), 0, st, score, prob, labels, n_rows, resid, bsum);
         arrol_launch(mlp_residual_finish_kernel, dim3(1), dim3(1), 0, st, bsum, n_rblocks, n_rows, loss_out, grad_b2);
-        r.resid = resid; r.delta_t = dt; r.delta_stride = p.n_pad; r.unit_partial = unit;
-        rc = launch_mlp_ring<kDelta>(r, dim3(n_tb, p.r_vt), st);
-        if (rc != ARROL_OK) return rc;
-        arrol_launch(reduce_rows_f32_kernel<0>, dim3((m + 31) / 32), dim3(256), 0, st, unit, n_tb * 4,
-                     static_cast<int64_t>(2) * m, static_cast<int64_t>(m), 1.f, grad_w2);
-        arrol_launch(reduce_rows_f32_kernel<0>, dim3((m + 31) / 32), dim3(256), 0, st, unit + m, n_tb * 4,
-                     static_cast<int64_t>(2) * m, static_cast<int64_t>(m), 1.f, grad_b1);
+        arrol_launch(mlp_delta_kernel, dim3(m), dim3(kDeltaThreads), 0, st, act, static_cast<int64_t>(p.n_pad), resid, w2,
+                     n_rows, p.n_pad, dt, grad_w2, grad_b1);
         arrol_launch(mlp_transpose_kernel, dim3(p.n_pad / 64, (d + 63) / 64), dim3(256), 0, st,
                      static_cast<const uint16_t*>(hidden), row_stride_elems, row_index, n_rows, d, p.n_pad, ht);
         float* rslab = reinterpret_cast<float*>(ws + p.off_rslab);
