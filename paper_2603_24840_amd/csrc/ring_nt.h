@@ -21,6 +21,15 @@
 //               matrix pipe never waits for an LDS round trip behind a barrier.
 // The barrier inside iteration i certifies the A part of slot i+2 and the B part of slot i+1 and
 // releases slot i-1 (A lines) / slot i-2.. for refilling; see the table in the loop for who loads what.
+//
+// B_KMAJOR = true is the "TN" form: B is given K-major, B[k][b] with the b index contiguous (row k starts
+// k * b_stride bytes after the base), so an operand that is stored rollout-major can be contracted over the
+// rollouts without a transposed copy.  A K32 slot then holds 32 k-rows of 256 b-values (512 bytes each, the
+// same 16 KiB), a load instruction moves two whole k-rows, and the B fragments come out of LDS through the
+// transposing read ds_read_b64_tr_b16: in each block of 16 lanes, lane 4e + q supplies the address of four
+// consecutive b-values of k-row e, and lane j receives the four k-values of b-value j (layout measured on
+// the device).  16-byte chunk c of k-row r sits at chunk position c ^ 4 (r % 4) of its row, so the four rows
+// that 32 lanes read together fall on different banks.
 #pragma once
 #include <type_traits>
 
@@ -64,6 +73,9 @@ struct Walk {
     int b_rows;               // B rows of this block that exist (1 .. BN)
     int n_tiles;              // A tiles to walk
     int n_k64;                // K extent / 64
+    int b_k_rows;             // B_KMAJOR only: k-rows of B that exist from b_base on (> 64 * (n_k64 - 1));
+                              // b_rows is then the number of valid b-values (a multiple of 8), b_stride the
+                              // bytes between k-rows
 };
 
 // Walks the tiles, accumulating into the caller's `acc` (cleared here first); `epilogue(acc, tile_index)` is
@@ -71,7 +83,7 @@ struct Walk {
 // tiles follow.  A caller that walks ONE tile can pass an empty epilogue and work on `acc` after the call:
 // on return every load into LDS and every fragment read has finished and the workgroup has passed a barrier,
 // so LDS is free for the caller too.
-template <class C, class Epilogue>
+template <class C, bool B_KMAJOR = false, class Epilogue>
 __device__ __forceinline__ void walk(const Walk& w, unsigned char* lds, f32x16 (&acc)[C::TM][C::TN], Epilogue&& epilogue) {
     constexpr int BM = C::BM, BN = C::BN, TM = C::TM, TN = C::TN, RING = C::RING;
     typedef __attribute__((address_space(3))) void* lds_ptr_t;
@@ -93,7 +105,18 @@ __device__ __forceinline__ void walk(const Walk& w, unsigned char* lds, f32x16 (
     // carries tile and K position, the lane offset the row inside the tile (clamped at the end of the
     // operand, so every load stays inside A and B) and the swizzled chunk.
     unsigned a_voff[C::G], b_voff[C::G];
-    {
+    int b_lrow[C::G];   // B_KMAJOR: this lane's k-row inside a K32 slot, per load group
+    if constexpr (B_KMAJOR) {
+        // one instruction = 2 k-rows x 512 bytes: lane -> (k-row lane/32, chunk position lane%32)
+        const int chunks_valid = w.b_rows >> 3;
+#pragma unroll
+        for (int g = 0; g < C::G; ++g) {
+            b_lrow[g] = (wave * C::G + g) * 2 + (lane >> 5);
+            int c = (lane & 31) ^ ((b_lrow[g] & 3) << 2);
+            c = c < chunks_valid ? c : chunks_valid - 1;
+            b_voff[g] = static_cast<unsigned>(c) * 16;
+        }
+    } else {
         const int rows_valid = w.b_rows;
 #pragma unroll
         for (int g = 0; g < C::G; ++g) {
@@ -131,14 +154,23 @@ __device__ __forceinline__ void walk(const Walk& w, unsigned char* lds, f32x16 (
         const int r0 = (wave * C::G + g) * 16;
         const unsigned dst = lds0 + s_h * C::SLOT_BYTES + (is_b ? BM * 64 : 0) + r0 * 64;
         const char* base = (is_b ? b_base : a_base) + h * 64;
-        const unsigned voff = is_b ? b_voff[g] : a_voff[g];
+        unsigned voff = is_b ? b_voff[g] : a_voff[g];
+        if constexpr (B_KMAJOR && is_b) {
+            // k-row of the pair, clamped to the last row that exists (the A operand is zero there)
+            const int left = w.b_k_rows - b_k64 * 64;                     // >= 1, wave-uniform
+            int r = h * 32 + b_lrow[g];
+            r = r < left ? r : left - 1;
+            voff += static_cast<unsigned>(r) * w.b_stride;
+            base = b_base;
+        }
         asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(dst) : "memory");
     };
     auto advance = [&](auto stream) {
         constexpr bool is_b = decltype(stream)::value;
         if (is_b) {
-            b_base += 128;
-            if (++b_k64 == n_k64) { b_k64 = 0; b_base -= static_cast<int64_t>(n_k64) * 128; }   // next A tile: B rewinds
+            const int64_t pair_bytes = B_KMAJOR ? static_cast<int64_t>(64) * w.b_stride : 128;
+            b_base += pair_bytes;
+            if (++b_k64 == n_k64) { b_k64 = 0; b_base -= n_k64 * pair_bytes; }   // next A tile: B rewinds
             b_slot = b_slot + 2 >= RING ? b_slot + 2 - RING : b_slot + 2;
             ++b_issued;
         } else {
@@ -178,8 +210,28 @@ __device__ __forceinline__ void walk(const Walk& w, unsigned char* lds, f32x16 (
     auto read_a = [&](bf16x8 (&fa)[TM], const unsigned char* base, int off, int m) {
         fa[m] = *reinterpret_cast<const bf16x8*>(base + off + m * 32 * 64);
     };
-    auto read_b = [&](bf16x8 (&fb)[TN], const unsigned char* base, int off, int j) {
-        fb[j] = *reinterpret_cast<const bf16x8*>(base + off + j * 32 * 64);
+    // B_KMAJOR: lane 16 b + 4 e + q of a wavefront addresses k-row 8 lh + 4 h2 + e (+ 16 per K16 step),
+    // b-values wn*64 + j*32 + 16 (b % 2) + 4 q .. + 3; block j = 1 is 4 chunks on, which the swizzle turns into ^ 64
+    int bt_off[2] = {0, 0};
+    if constexpr (B_KMAJOR) {
+        const int e = (lane & 15) >> 2, q = lane & 3;
+        const int chunk = wn * (BN / C::WN / 8) + 2 * ((lane >> 4) & 1) + (q >> 1);
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2)
+            bt_off[h2] = BM * 64 + (8 * lh + 4 * h2 + e) * 512 + ((chunk ^ (e << 2)) << 4) + (q & 1) * 8;
+    }
+    auto read_b = [&](bf16x8 (&fb)[TN], const unsigned char* base, int k16, int j) {   // k16: K16 step 0 / 1 of the slot
+        if constexpr (B_KMAJOR) {
+            typedef short s16x4 __attribute__((ext_vector_type(4)));
+            typedef short s16x8 __attribute__((ext_vector_type(8)));
+            typedef __attribute__((address_space(3))) s16x4* lds_s16x4_t;
+            const int step = k16 * 16 * 512;
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t)(base + ((bt_off[0] ^ (j << 6)) + step)));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t)(base + ((bt_off[1] ^ (j << 6)) + step)));
+            fb[j] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        } else {
+            fb[j] = *reinterpret_cast<const bf16x8*>(base + (k16 ? b_off1 : b_off0) + j * 32 * 64);
+        }
     };
     auto mma = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], int x) {
         acc[x / TN][x % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[x / TN], fb[x % TN], acc[x / TN][x % TN], 0, 0, 0);
@@ -197,7 +249,7 @@ __device__ __forceinline__ void walk(const Walk& w, unsigned char* lds, f32x16 (
         if (n_pairs > 1) wait_vmcnt<C::LOADS>(); else wait_vmcnt<0>();
         __syncthreads();
 #pragma unroll
-        for (int j = 0; j < TN; ++j) read_b(fb0, lds, b_off0, j);
+        for (int j = 0; j < TN; ++j) read_b(fb0, lds, 0, j);
 #pragma unroll
         for (int m = 0; m < TM; ++m) read_a(fa0, lds, a_off0, m);
     }
@@ -214,7 +266,7 @@ __device__ __forceinline__ void walk(const Walk& w, unsigned char* lds, f32x16 (
         // ---- K16 step 0 -------------------------------------------------------------------------
         mma(fa0, fb0, 0); mma(fa0, fb0, 1);
         __builtin_amdgcn_sched_barrier(0);
-        read_b(fb1, cur, b_off1, 0); read_b(fb1, cur, b_off1, 1);
+        read_b(fb1, cur, 1, 0); read_b(fb1, cur, 1, 1);
         if (loads) issue_one(stream, 0);
         __builtin_amdgcn_sched_barrier(0);
         mma(fa0, fb0, 2); mma(fa0, fb0, 3);
@@ -241,7 +293,7 @@ __device__ __forceinline__ void walk(const Walk& w, unsigned char* lds, f32x16 (
         if (loads) wait_vmcnt<3>(); else wait_vmcnt<0>();
         __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0) only
         __syncthreads();
-        read_b(fb0, nxt, b_off0, 0); read_b(fb0, nxt, b_off0, 1);           // B part of slot i+1: certified just now
+        read_b(fb0, nxt, 0, 0); read_b(fb0, nxt, 0, 1);           // B part of slot i+1: certified just now
         read_a(fa0, nxt, a_off0, 2); read_a(fa0, nxt, a_off0, 3);
         __builtin_amdgcn_sched_barrier(0);
         mma(fa1, fb1, 4); mma(fa1, fb1, 5);

@@ -422,13 +422,14 @@ __global__ __launch_bounds__(256) void score_mlp_small_finish_kernel(const float
 //            for the gradient call the same pass also keeps the activations a = relu(pre) in fp32, unit-major
 //            (the accumulator's own layout: 32 lanes = 32 consecutive rollouts), so that nothing is recomputed:
 //            delta^T = r w2 [a > 0] and the per-unit sums are then one streaming pass (mlp_delta_kernel);
-//   wgrad    A = delta^T [m, n_pad], B = H^T [d, n_pad] over K = rollouts (split): fp32 tile stores.
+//   wgrad    A = delta^T [m, n_pad], B = the hidden states themselves, [N, d] = K-major (ring_nt's TN form, no
+//            transposed copy), over K = rollouts (split): fp32 tile stores.
 using RingCfg = ring_nt::RingTile<256, 256, 2, 4>;
 
 struct MlpRingArgs {
     const uint16_t* a; unsigned a_stride;   // A rows (bytes between rows), a_rows of them
-    const uint16_t* b; unsigned b_stride;   // B rows, b_rows of them
-    int a_rows, b_rows, n_k64, k64_per_split;
+    const uint16_t* b; unsigned b_stride;   // B rows, b_rows of them; wgrad: k-rows of b_rows values, b_k_rows of them
+    int a_rows, b_rows, b_k_rows, n_k64, k64_per_split;
     const float* b1; const float* w2;
     float* partial;              // forward: [gridDim.y][b_rows]
     float* act_t; int64_t act_stride;       // forward for the gradient: relu(pre), [a_rows][act_stride] fp32
@@ -450,19 +451,22 @@ __global__ __launch_bounds__(RingCfg::NT) void mlp_ring_kernel(MlpRingArgs a) {
 
     ring_nt::Walk w;
     w.a_base = reinterpret_cast<const char*>(a.a) + static_cast<int64_t>(vt) * BM * a.a_stride + static_cast<int64_t>(k64_lo) * 128;
-    w.b_base = reinterpret_cast<const char*>(a.b) + static_cast<int64_t>(tb) * BN * a.b_stride + static_cast<int64_t>(k64_lo) * 128;
+    w.b_base = MODE == kWgrad
+                   ? reinterpret_cast<const char*>(a.b) + static_cast<int64_t>(k64_lo) * 64 * a.b_stride + static_cast<int64_t>(tb) * BN * 2
+                   : reinterpret_cast<const char*>(a.b) + static_cast<int64_t>(tb) * BN * a.b_stride + static_cast<int64_t>(k64_lo) * 128;
     w.a_stride = a.a_stride;
     w.b_stride = a.b_stride;
     w.a_rows = a.a_rows - vt * BM;
     w.b_rows = a.b_rows - tb * BN < BN ? a.b_rows - tb * BN : BN;
     w.n_tiles = 1;
-    w.n_k64 = k64_hi - k64_lo;
+    w.n_k64 = k64_hi > k64_lo ? k64_hi - k64_lo : 0;
+    w.b_k_rows = a.b_k_rows - k64_lo * 64;
 
     const int unit0 = vt * BM + wm * (BM / C::WM);           // first A row of this wavefront
     const int row0 = tb * BN + wn * (BN / C::WN);            // first B row of this wavefront
     float part[TN] = {0.f, 0.f};
     f32x16 acc[TM][TN];
-    ring_nt::walk<C>(w, lds, acc, [](f32x16 (&)[TM][TN], int) {});   // one tile: the epilogue runs here, after the walk
+    ring_nt::walk<C, MODE == kWgrad>(w, lds, acc, [](f32x16 (&)[TM][TN], int) {});   // one tile: the epilogue runs here, after the walk
     {
         // acc[i][j][v]: A row unit0 + i*32 + (v/4)*8 + lh*4 + v%4, B row row0 + j*32 + l31
 #pragma unroll
@@ -829,13 +833,12 @@ extern "C" int arrol_score_mlp_grad(const void* hidden, int64_t row_stride_elems
         arrol_launch(mlp_residual_finish_kernel, dim3(1), dim3(1), 0, st, bsum, n_rblocks, n_rows, loss_out, grad_b2);
         arrol_launch(mlp_delta_kernel, dim3(m), dim3(kDeltaThreads), 0, st, act, static_cast<int64_t>(p.n_pad), resid, w2,
                      n_rows, p.n_pad, dt, grad_w2, grad_b1);
-        arrol_launch(mlp_transpose_kernel, dim3(p.n_pad / 64, (d + 63) / 64), dim3(256), 0, st,
-                     static_cast<const uint16_t*>(hidden), row_stride_elems, row_index, n_rows, d, p.n_pad, ht);
         float* rslab = reinterpret_cast<float*>(ws + p.off_rslab);
         MlpRingArgs g = {};
         g.a = dt; g.a_stride = static_cast<unsigned>(p.n_pad) * 2; g.a_rows = m;
-        g.b = ht; g.b_stride = static_cast<unsigned>(p.n_pad) * 2; g.b_rows = d;
-        g.n_k64 = p.n_kc; g.k64_per_split = p.r_k64_per_split;
+        g.b = static_cast<const uint16_t*>(hidden); g.b_stride = static_cast<unsigned>(row_stride_elems * 2);
+        g.b_rows = d; g.b_k_rows = n_rows;
+        g.n_k64 = (n_rows + 63) / 64; g.k64_per_split = p.r_k64_per_split;
         g.c_out = p.r_splits > 1 ? rslab : grad_w1; g.c_stride = d;
         rc = launch_mlp_ring<kWgrad>(g, dim3(p.r_cb, p.r_vt, p.r_splits), st);
         if (rc != ARROL_OK) return rc;

@@ -193,7 +193,8 @@ def check_mlp_grad(A, hidden, w1, b1, w2, b2, labels, row_index=None):
 
 @pytest.mark.parametrize("n,d,m", [(1, 8, 1), (32, 256, 64), (130, 264, 100), (300, 1024, 257), (512, 2048, 512),
                                    (1500, 512, 300),
-                                   (4500, 128, 300), (4097, 64, 7), (5000, 192, 512)])     # beyond 4,096 rows: the ring-pipeline kernels
+                                   (4500, 128, 300), (4097, 64, 7), (5000, 192, 512),      # beyond 4,096 rows: the ring-pipeline kernels
+                                   (4200, 320, 70), (8195, 576, 260)])                     # ... more than one 256-column block of dL/dW1
 def test_score_mlp_grad_matches_oracle(A, n, d, m):
     print("[case] score_mlp_grad n=%d d=%d m=%d" % (n, d, m), flush=True)
     hidden, w1, b1, w2, labels = mlp_case(n, d, m, seed=n + d + m)
@@ -218,6 +219,20 @@ def test_score_mlp_grad_gathered_rows_no_bias_dead_units_and_empty_batch(A):
     torch.cuda.synchronize()
     assert float(out["loss"]) == 0.0 and float(out["grad_b2"]) == 0.0
     assert not out["grad_w1"].any() and not out["grad_b1"].any() and not out["grad_w2"].any()
+
+
+def test_score_mlp_grad_large_batch_strided_rows_and_reproducible(A):
+    """Ring-pipeline path on rows that are a view into a wider buffer (dL/dW1 contracts the hidden states in
+    place, rollout-major); two calls give identical bits."""
+    print("[case] score_mlp_grad n=4300 d=192 of 256 m=130 strided", flush=True)
+    hidden, w1, b1, w2, labels = mlp_case(4300, 192, 130, seed=21)
+    wide = torch.full((4300, 256), float("nan"), dtype=torch.bfloat16, device=DEV)   # what lies beside the rows is never read
+    wide[:, :192] = hidden
+    o1 = check_mlp_grad(A, wide[:, :192], w1, b1, w2 * 2.0, 0.25, labels)
+    o2 = A.arrol_score_mlp_grad(wide[:, :192], w1, b1, w2 * 2.0, 0.25, labels)
+    torch.cuda.synchronize()
+    for k in o1:
+        assert torch.equal(o1[k], o2[k]), k
 
 
 def test_score_mlp_grad_is_reproducible_and_trains(A):
