@@ -340,7 +340,7 @@ constexpr int kSmallThreads = 64;       // one wavefront per workgroup: its lane
 __global__ __launch_bounds__(kSmallThreads) void score_mlp_small_kernel(
     const uint16_t* __restrict__ hidden, int64_t row_stride, const int64_t* __restrict__ row_index,
     const uint16_t* __restrict__ w1, const float* __restrict__ b1, const float* __restrict__ w2, int n_rows, int d, int m,
-    int n_ub, float* __restrict__ partial) {
+    int n_ub, float* __restrict__ partial, float* __restrict__ act_t, int64_t act_stride) {
     const int lane = threadIdx.x & 63;
     const int l31 = lane & 31, lh = lane >> 5;
     const int ub = blockIdx.y;                      // unit block
@@ -388,7 +388,10 @@ __global__ __launch_bounds__(kSmallThreads) void score_mlp_small_kernel(
         const bool live = u < m;
         const float bias = (live && b1) ? b1[u] : 0.f;
         const float w = live ? w2[u] : 0.f;
-        part = fmaf(fmaxf(acc[v] + bias, 0.f), w, part);
+        const float act = fmaxf(acc[v] + bias, 0.f);
+        part = fmaf(act, w, part);
+        // the gradient call keeps relu(pre), unit-major (see mlp_delta_kernel)
+        if (act_t && live && r0 + l31 < n_rows) act_t[static_cast<int64_t>(u) * act_stride + r0 + l31] = act;
     }
     part += __shfl_xor(part, 32, ARROL_WAVE);       // the two lane halves hold different units of one rollout
     if (lh == 0 && r0 + l31 < n_rows) partial[static_cast<int64_t>(ub) * n_rows + r0 + l31] = part;
@@ -527,6 +530,11 @@ int launch_mlp_ring(const MlpRingArgs& a, dim3 grid, hipStream_t st) {
 // the ring kernels address a lane's row with a 32-bit byte offset inside a 256-row tile
 bool ring_applies(int n_rows, int d, int64_t row_stride_elems, const int64_t* row_index) {
     return n_rows > kSmallMaxRows && d % 64 == 0 && row_index == nullptr && row_stride_elems * 2 * 256 < (1ll << 31);
+}
+
+// dL/dW1 on the ring pipeline's K-major B form: any batch size, rows addressed in place
+bool ring_wgrad_applies(int d, int64_t row_stride_elems, const int64_t* row_index) {
+    return d % 64 == 0 && row_index == nullptr && row_stride_elems * 2 * 256 < (1ll << 31);
 }
 
 // r_i = (q_i - y_i) / N and the loss: one workgroup per 1024 rows writes its two partial sums, the second
@@ -703,9 +711,9 @@ GradPlan make_grad_plan(int n_rows, int d, int m) {
     p.r_k64_per_split = (p.n_kc + rs - 1) / rs;
     p.r_splits = (p.n_kc + p.r_k64_per_split - 1) / p.r_k64_per_split;
     p.off_rslab = o;
-    if (n_rows > kSmallMaxRows && d % 64 == 0 && p.r_splits > 1) o = align256(o + sizeof(float) * static_cast<size_t>(p.r_splits) * m * d);
-    p.off_act = o;                        // ring forward pass: kept activations, fp32 [m][n_pad]
-    if (n_rows > kSmallMaxRows && d % 64 == 0) o = align256(o + sizeof(float) * static_cast<size_t>(m) * p.n_pad);
+    if (d % 64 == 0 && p.r_splits > 1) o = align256(o + sizeof(float) * static_cast<size_t>(p.r_splits) * m * d);
+    p.off_act = o;                        // small-batch / ring forward pass: kept activations, fp32 [m][n_pad]
+    if (d % 64 == 0) o = align256(o + sizeof(float) * static_cast<size_t>(m) * p.n_pad);
     p.total = o;
     return p;
 }
@@ -762,7 +770,7 @@ extern "C" int arrol_score_mlp(const void* hidden, int64_t row_stride_elems, con
         float* partial = static_cast<float*>(workspace);
         arrol_launch(score_mlp_small_kernel, dim3((n_rows + 31) / 32, n_ub), dim3(kSmallThreads), 0, st,
                      static_cast<const uint16_t*>(hidden), row_stride_elems, row_index, static_cast<const uint16_t*>(w1),
-                     b1, w2, n_rows, d, m, n_ub, partial);
+                     b1, w2, n_rows, d, m, n_ub, partial, static_cast<float*>(nullptr), static_cast<int64_t>(0));
         if (arrol_launch_failed()) return arrol_launch_status();
         arrol_launch(score_mlp_small_finish_kernel, dim3((n_rows + 255) / 256), dim3(256), 0, st, partial, n_ub,
                      n_rows, b2, score_out, prob_out);
@@ -815,71 +823,77 @@ extern "C" int arrol_score_mlp_grad(const void* hidden, int64_t row_stride_elems
     float* unit = reinterpret_cast<float*>(ws + p.off_unit);
     float* slab = reinterpret_cast<float*>(ws + p.off_slab);
 
+    // forward pass.  Batches beyond kSmallMaxRows rows: the ring pipeline; smaller ones: one wavefront per block;
+    // both keep relu(pre) for the backward pass.  Otherwise (d not a multiple of 64, or gathered rows of a large
+    // batch) the one-launch tile kernel, whose pre-activations are recomputed below.
+    MlpArgs a = {};
+    a.hidden = static_cast<const uint16_t*>(hidden); a.row_stride = row_stride_elems; a.row_index = row_index;
+    a.w1 = static_cast<const uint16_t*>(w1); a.a_stride = d; a.b1 = b1; a.w2 = w2; a.b2 = b2;
+    a.n_rows = n_rows; a.d = d; a.m = m; a.score_out = score; a.prob_out = prob;
+    float* act = reinterpret_cast<float*>(ws + p.off_act);
+    float* partial = reinterpret_cast<float*>(ws + p.off_small);
+    bool kept = true;
+    int rc = ARROL_OK;
     if (ring_applies(n_rows, d, row_stride_elems, row_index)) {
-        // large batch: every contraction on the ring pipeline
-        const int n_tb = (n_rows + 255) / 256;
-        float* partial = reinterpret_cast<float*>(ws + p.off_small);
         MlpRingArgs r = {};
-        r.a = static_cast<const uint16_t*>(w1); r.a_stride = static_cast<unsigned>(d) * 2; r.a_rows = m;
-        r.b = static_cast<const uint16_t*>(hidden); r.b_stride = static_cast<unsigned>(row_stride_elems * 2); r.b_rows = n_rows;
+        r.a = a.w1; r.a_stride = static_cast<unsigned>(d) * 2; r.a_rows = m;
+        r.b = a.hidden; r.b_stride = static_cast<unsigned>(row_stride_elems * 2); r.b_rows = n_rows;
         r.n_k64 = d / 64; r.b1 = b1; r.w2 = w2; r.partial = partial;
-        float* act = reinterpret_cast<float*>(ws + p.off_act);
         r.act_t = act; r.act_stride = p.n_pad;
-        int rc = launch_mlp_ring<kForwardKeep>(r, dim3(n_tb, p.r_vt), st);
+        rc = launch_mlp_ring<kForwardKeep>(r, dim3((n_rows + 255) / 256, p.r_vt), st);
         if (rc != ARROL_OK) return rc;
         arrol_launch(score_mlp_small_finish_kernel, dim3((n_rows + 255) / 256), dim3(256), 0, st, partial, p.r_vt,
                      n_rows, b2, score, prob);
-        arrol_launch(mlp_residual_kernel, dim3(n_rblocks), dim3(1024), 0, st, score, prob, labels, n_rows, resid, bsum);
-        arrol_launch(mlp_residual_finish_kernel, dim3(1), dim3(1), 0, st, bsum, n_rblocks, n_rows, loss_out, grad_b2);
+    } else if (d % 64 == 0 && n_rows <= kSmallMaxRows) {
+        const int n_ub = (m + 31) / 32;
+        arrol_launch(score_mlp_small_kernel, dim3((n_rows + 31) / 32, n_ub), dim3(kSmallThreads), 0, st,
+                     a.hidden, row_stride_elems, row_index, a.w1, b1, w2, n_rows, d, m, n_ub, partial, act,
+                     static_cast<int64_t>(p.n_pad));
+        arrol_launch(score_mlp_small_finish_kernel, dim3((n_rows + 255) / 256), dim3(256), 0, st, partial, n_ub,
+                     n_rows, b2, score, prob);
+    } else {
+        kept = false;
+        rc = launch_mlp<kForward>(a, dim3(p.n_rb), st);
+        if (rc != ARROL_OK) return rc;
+    }
+    if (arrol_launch_failed()) return arrol_launch_status();
+    // residuals and loss
+    arrol_launch(mlp_residual_kernel, dim3(n_rblocks), dim3(1024), 0, st, score, prob, labels, n_rows, resid, bsum);
+    arrol_launch(mlp_residual_finish_kernel, dim3(1), dim3(1), 0, st, bsum, n_rblocks, n_rows, loss_out, grad_b2);
+    // delta^T and the per-unit sums
+    if (kept) {
         arrol_launch(mlp_delta_kernel, dim3(m), dim3(kDeltaThreads), 0, st, act, static_cast<int64_t>(p.n_pad), resid, w2,
                      n_rows, p.n_pad, dt, grad_w2, grad_b1);
+    } else {
+        a.resid = resid; a.delta_t = dt; a.delta_stride = p.n_pad; a.unit_partial = unit;
+        rc = launch_mlp<kDelta>(a, dim3(p.n_rb), st);
+        if (rc != ARROL_OK) return rc;
+        arrol_launch(reduce_rows_f32_kernel<0>, dim3((m + 31) / 32), dim3(256), 0, st, unit, p.n_rb,
+                     static_cast<int64_t>(2) * m, static_cast<int64_t>(m), 1.f, grad_w2);
+        arrol_launch(reduce_rows_f32_kernel<0>, dim3((m + 31) / 32), dim3(256), 0, st, unit + m, p.n_rb,
+                     static_cast<int64_t>(2) * m, static_cast<int64_t>(m), 1.f, grad_b1);
+    }
+    if (arrol_launch_failed()) return arrol_launch_status();
+    const int64_t width = static_cast<int64_t>(m) * d;
+    if (ring_wgrad_applies(d, row_stride_elems, row_index)) {
+        // dL/dW1 = delta^T . H over the rollouts, the hidden states read in place
         float* rslab = reinterpret_cast<float*>(ws + p.off_rslab);
         MlpRingArgs g = {};
         g.a = dt; g.a_stride = static_cast<unsigned>(p.n_pad) * 2; g.a_rows = m;
-        g.b = static_cast<const uint16_t*>(hidden); g.b_stride = static_cast<unsigned>(row_stride_elems * 2);
+        g.b = a.hidden; g.b_stride = static_cast<unsigned>(row_stride_elems * 2);
         g.b_rows = d; g.b_k_rows = n_rows;
         g.n_k64 = (n_rows + 63) / 64; g.k64_per_split = p.r_k64_per_split;
         g.c_out = p.r_splits > 1 ? rslab : grad_w1; g.c_stride = d;
         rc = launch_mlp_ring<kWgrad>(g, dim3(p.r_cb, p.r_vt, p.r_splits), st);
         if (rc != ARROL_OK) return rc;
-        if (p.r_splits > 1) {
-            const int64_t width = static_cast<int64_t>(m) * d;
+        if (p.r_splits > 1)
             arrol_launch(reduce_rows_f32_kernel<0>, dim3(static_cast<unsigned>((width + 31) / 32)), dim3(256), 0, st,
                          rslab, p.r_splits, width, width, 1.f, grad_w1);
-        }
         return arrol_launch_status();
     }
-    // forward pass, residuals and loss
-    MlpArgs a = {};
-    a.hidden = static_cast<const uint16_t*>(hidden); a.row_stride = row_stride_elems; a.row_index = row_index;
-    a.w1 = static_cast<const uint16_t*>(w1); a.a_stride = d; a.b1 = b1; a.w2 = w2; a.b2 = b2;
-    a.n_rows = n_rows; a.d = d; a.m = m; a.score_out = score; a.prob_out = prob;
-    int rc = ARROL_OK;
-    if (p.total > p.off_small) {          // small batch: the wavefront-per-block forward pass
-        const int n_ub = (m + 31) / 32;
-        float* partial = reinterpret_cast<float*>(ws + p.off_small);
-        arrol_launch(score_mlp_small_kernel, dim3((n_rows + 31) / 32, n_ub), dim3(kSmallThreads), 0, st,
-                     a.hidden, row_stride_elems, row_index, a.w1, b1, w2, n_rows, d, m, n_ub, partial);
-        arrol_launch(score_mlp_small_finish_kernel, dim3((n_rows + 255) / 256), dim3(256), 0, st, partial, n_ub,
-                     n_rows, b2, score, prob);
-        if (arrol_launch_failed()) return arrol_launch_status();
-    } else {
-        rc = launch_mlp<kForward>(a, dim3(p.n_rb), st);
-        if (rc != ARROL_OK) return rc;
-    }
-    arrol_launch(mlp_residual_kernel, dim3(n_rblocks), dim3(1024), 0, st, score, prob, labels, n_rows, resid, bsum);
-    arrol_launch(mlp_residual_finish_kernel, dim3(1), dim3(1), 0, st, bsum, n_rblocks, n_rows, loss_out, grad_b2);
-    // delta^T and the per-unit sums
-    a.resid = resid; a.delta_t = dt; a.delta_stride = p.n_pad; a.unit_partial = unit;
-    rc = launch_mlp<kDelta>(a, dim3(p.n_rb), st);
-    if (rc != ARROL_OK) return rc;
-    arrol_launch(reduce_rows_f32_kernel<0>, dim3((m + 31) / 32), dim3(256), 0, st, unit, p.n_rb,
-                       static_cast<int64_t>(2) * m, static_cast<int64_t>(m), 1.f, grad_w2);
-    arrol_launch(reduce_rows_f32_kernel<0>, dim3((m + 31) / 32), dim3(256), 0, st, unit + m, p.n_rb,
-                       static_cast<int64_t>(2) * m, static_cast<int64_t>(m), 1.f, grad_b1);
-    // H^T, then dL/dW1 = delta^T . H over the rollouts
+    // gathered rows or d not a multiple of 64: H^T, then the tile kernel
     arrol_launch(mlp_transpose_kernel, dim3(p.n_pad / 64, (d + 63) / 64), dim3(256), 0, st,
-                       static_cast<const uint16_t*>(hidden), row_stride_elems, row_index, n_rows, d, p.n_pad, ht);
+                 a.hidden, row_stride_elems, row_index, n_rows, d, p.n_pad, ht);
     MlpArgs g = {};
     g.hidden = ht; g.row_stride = p.n_pad; g.row_index = nullptr;
     g.w1 = dt; g.a_stride = p.n_pad;
@@ -887,10 +901,8 @@ extern "C" int arrol_score_mlp_grad(const void* hidden, int64_t row_stride_elems
     g.c_out = p.splits > 1 ? slab : grad_w1; g.c_stride = d; g.kc_per_split = p.kc_per_split;
     rc = launch_mlp<kWgrad>(g, dim3(p.n_cb, p.splits, p.n_groups), st);
     if (rc != ARROL_OK) return rc;
-    if (p.splits > 1) {
-        const int64_t width = static_cast<int64_t>(m) * d;
+    if (p.splits > 1)
         arrol_launch(reduce_rows_f32_kernel<0>, dim3(static_cast<unsigned>((width + 31) / 32)), dim3(256), 0, st,
-                           slab, p.splits, width, width, 1.f, grad_w1);
-    }
+                     slab, p.splits, width, width, 1.f, grad_w1);
     return arrol_launch_status();
 }
