@@ -392,7 +392,8 @@ def time_extras(A, W, cfg, dev, torch, lp_hidden, lm_head, targets, cu, reps=10)
                                 "kernel durations are in profiles/"}
     mws = torch.empty(max(256, A.lib().arrol_score_mlp_grad_workspace_bytes(N, d, m)), dtype=torch.uint8, device=dev)
     ms = timed(lambda: A.arrol_score_mlp_grad(hidden, w1, b1, w2, 0.0, labels, workspace=mws))
-    out["score_mlp_grad"] = {"ms": ms, "shape": "N=%d, d=%d, m=%d" % (N, d, m), "TFLOPs": 6.0 * N * d * m / ms / 1e9}
+    out["score_mlp_grad"] = {"ms": ms, "shape": "N=%d, d=%d, m=%d" % (N, d, m), "TFLOPs": 4.0 * N * d * m / ms / 1e9,
+                             "flops": "two contractions (forward, dL/dW1): 4*N*d*m; the pre-activations are kept, not recomputed"}
     # the MLP head at the test-time-scaling shape of the largest configuration
     big = W.CONFIGS["qwen8b"]
     nb = big.vote_q * big.vote_c
@@ -405,7 +406,8 @@ def time_extras(A, W, cfg, dev, torch, lp_hidden, lm_head, targets, cu, reps=10)
     bws = torch.empty(max(256, A.lib().arrol_score_mlp_grad_workspace_bytes(nb, big.d, m)), dtype=torch.uint8, device=dev)
     ms = timed(lambda: A.arrol_score_mlp_grad(hb, w1b, b1, w2, 0.0, lb, workspace=bws))
     out["score_mlp_grad_test_time_shape"] = {"ms": ms, "shape": "N=%d, d=%d, m=%d" % (nb, big.d, m),
-                                             "TFLOPs": 6.0 * nb * big.d * m / ms / 1e9}
+                                             "TFLOPs": 4.0 * nb * big.d * m / ms / 1e9,
+                                             "flops": "two contractions (forward, dL/dW1): 4*N*d*m"}
     del hb, w1b, lb, bws
     gws = torch.empty(max(16, A.lib().arrol_score_grad_workspace_bytes(N, d)), dtype=torch.uint8, device=dev)
     ms = timed(lambda: A.arrol_score_grad(hidden, w, bias, labels, workspace=gws))
