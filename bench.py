@@ -390,7 +390,7 @@ def time_extras(A, W, cfg, dev, torch, lp_hidden, lm_head, targets, cu, reps=10)
                         "path": "small-batch (wavefront per 32x32 block + finish)" if sws_bytes else "tile kernel",
                         "note": "HIP-event mean over back-to-back calls from Python: a floor of ~20 us per call is host launch cost; "
                                 "kernel durations are in profiles/"}
-    mws = torch.empty(max(256, A.lib().arrol_score_mlp_grad_workspace_bytes(N, d, m)), dtype=torch.uint8, device=dev)
+    mws = torch.empty(max(256, A.lib().arrol_score_mlp_grad_workspace_bytes(N, d, m, 1)), dtype=torch.uint8, device=dev)
     ms = timed(lambda: A.arrol_score_mlp_grad(hidden, w1, b1, w2, 0.0, labels, workspace=mws))
     out["score_mlp_grad"] = {"ms": ms, "shape": "N=%d, d=%d, m=%d" % (N, d, m), "TFLOPs": 4.0 * N * d * m / ms / 1e9,
                              "flops": "two contractions (forward, dL/dW1): 4*N*d*m; the pre-activations are kept, not recomputed"}
@@ -403,7 +403,7 @@ def time_extras(A, W, cfg, dev, torch, lp_hidden, lm_head, targets, cu, reps=10)
     ms = timed(lambda: A.arrol_score_mlp(hb, w1b, b1, w2))
     out["score_mlp_test_time_shape"] = {"ms": ms, "shape": "N=%d, d=%d, m=%d" % (nb, big.d, m),
                                         "TFLOPs": 2.0 * nb * big.d * m / ms / 1e9}
-    bws = torch.empty(max(256, A.lib().arrol_score_mlp_grad_workspace_bytes(nb, big.d, m)), dtype=torch.uint8, device=dev)
+    bws = torch.empty(max(256, A.lib().arrol_score_mlp_grad_workspace_bytes(nb, big.d, m, 1)), dtype=torch.uint8, device=dev)
     ms = timed(lambda: A.arrol_score_mlp_grad(hb, w1b, b1, w2, 0.0, lb, workspace=bws))
     out["score_mlp_grad_test_time_shape"] = {"ms": ms, "shape": "N=%d, d=%d, m=%d" % (nb, big.d, m),
                                              "TFLOPs": 4.0 * nb * big.d * m / ms / 1e9,

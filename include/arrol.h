@@ -363,17 +363,21 @@ int arrol_score_grad(const void* hidden, int64_t row_stride_elems, const int64_t
  *   dL/db2 = sum_i r_i,  dL/dw2 = sum_i r_i a_i,  dL/db1 = sum_i delta_i,  dL/dW1 = sum_i delta_i h_i^T
  * hidden, row_stride_elems, row_index, w1, b1, w2, b2, n_rows, d, m as in arrol_score_mlp; labels fp32 [n_rows].
  * loss_out NULL or fp32 [1]; grad_w1 fp32 [m, d]; grad_b1, grad_w2 fp32 [m]; grad_b2 NULL or fp32 [1].
- * The pre-activations are recomputed on the matrix cores; delta is rounded to bf16 before the contraction
- * over the rollouts (bf16 products, fp32 accumulation), everything else is fp32; sums in a fixed order.
+ * delta is rounded to bf16 before the contraction over the rollouts (bf16 products, fp32 accumulation);
+ * everything else is fp32; sums in a fixed order (bit-reproducible run to run).
+ * delta_terms: 1 = delta as one bf16 value (relative rounding 2^-9 per term of dL/dW1); 2 = delta as the sum
+ * of two bf16 values, hi = bf16(delta) and lo = bf16(delta - hi), contracted one after the other (relative
+ * rounding 2^-17: dL/dW1 to fp32 accuracy, at twice the cost of that contraction).  Other values -> ARROL_EINVAL.
  * n_rows == 0 writes zeros.
- * workspace: arrol_score_mlp_grad_workspace_bytes(n_rows, d, m) bytes, 256-byte aligned, caller-owned.
+ * workspace: arrol_score_mlp_grad_workspace_bytes(n_rows, d, m, delta_terms) bytes, 256-byte aligned,
+ * caller-owned, contents undefined afterwards; too small or NULL -> ARROL_EWORKSPACE.
  */
-size_t arrol_score_mlp_grad_workspace_bytes(int32_t n_rows, int32_t d, int32_t m);
+size_t arrol_score_mlp_grad_workspace_bytes(int32_t n_rows, int32_t d, int32_t m, int32_t delta_terms);
 int arrol_score_mlp_grad(const void* hidden, int64_t row_stride_elems, const int64_t* row_index,
                          const void* w1, const float* b1, const float* w2, float b2, const float* labels,
                          int32_t n_rows, int32_t d, int32_t m, float* loss_out, float* grad_w1,
-                         float* grad_b1, float* grad_w2, float* grad_b2, void* workspace,
-                         size_t workspace_bytes, void* stream);
+                         float* grad_b1, float* grad_w2, float* grad_b2, int32_t delta_terms,
+                         void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * One AdamW update in place (the paper names no optimizer; AdamW with decoupled weight decay is this

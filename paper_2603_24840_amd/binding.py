@@ -48,9 +48,9 @@ _SIGNATURES = {
     "arrol_score_mlp": (ctypes.c_int, [_vp, _i64, _vp, _vp, _vp, _vp, _f32, _i32, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
     "arrol_score_grad_workspace_bytes": (_sz, [_i32, _i32]),
     "arrol_score_grad": (ctypes.c_int, [_vp, _i64, _vp, _vp, _f32, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _sz, _vp]),
-    "arrol_score_mlp_grad_workspace_bytes": (_sz, [_i32, _i32, _i32]),
+    "arrol_score_mlp_grad_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32]),
     "arrol_score_mlp_grad": (ctypes.c_int, [_vp, _i64, _vp, _vp, _vp, _vp, _f32, _vp, _i32, _i32, _i32, _vp, _vp, _vp,
-                                            _vp, _vp, _vp, _sz, _vp]),
+                                            _vp, _vp, _i32, _vp, _sz, _vp]),
     "arrol_adamw_step": (ctypes.c_int, [_vp, _vp, _vp, _vp, _i64, _i32, _f32, _f32, _f32, _f32, _f32, _vp, _vp]),
     "arrol_select": (ctypes.c_int, [_vp, _i32, _i32, _i32, _f32, _vp, _vp, _vp]),
     "arrol_compact_workspace_bytes": (_sz, [_i32]),
@@ -216,9 +216,9 @@ def arrol_score_grad(hidden, w, bias, labels, row_index=None, workspace=None, st
 
 
 @_on_stream
-def arrol_score_mlp_grad(hidden, w1, b1, w2, b2, labels, row_index=None, workspace=None, stream=None):
+def arrol_score_mlp_grad(hidden, w1, b1, w2, b2, labels, row_index=None, delta_terms=1, workspace=None, stream=None):
     """Cross-entropy loss of the MLP head and its gradients: -> dict(loss [1], grad_w1 [m, d], grad_b1 [m],
-    grad_w2 [m], grad_b2 [1]), all fp32."""
+    grad_w2 [m], grad_b2 [1]), all fp32.  delta_terms=2: dL/dW1 to fp32 accuracy (two bf16 terms per delta)."""
     if hidden.dim() != 2 or hidden.dtype != torch.bfloat16 or not hidden.is_cuda or hidden.stride(1) != 1:
         raise TypeError("hidden must be a 2-D bf16 GPU tensor with contiguous rows")
     d = hidden.shape[1]
@@ -228,7 +228,8 @@ def arrol_score_mlp_grad(hidden, w1, b1, w2, b2, labels, row_index=None, workspa
         raise ValueError("w1 must be [m, d], b1 and w2 [m], labels [n]")
     dev = hidden.device
     if workspace is None:
-        workspace = torch.empty(max(lib().arrol_score_mlp_grad_workspace_bytes(n, d, m), 256), dtype=torch.uint8, device=dev)
+        workspace = torch.empty(max(lib().arrol_score_mlp_grad_workspace_bytes(n, d, m, int(delta_terms)), 256), dtype=torch.uint8,
+                                device=dev)
     out = dict(loss=torch.empty(1, dtype=torch.float32, device=dev),
                grad_w1=torch.empty((m, d), dtype=torch.float32, device=dev),
                grad_b1=torch.empty(m, dtype=torch.float32, device=dev),
@@ -240,7 +241,8 @@ def arrol_score_mlp_grad(hidden, w1, b1, w2, b2, labels, row_index=None, workspa
                                     _ptr(w2, torch.float32, "w2"), float(b2), _ptr(labels, torch.float32, "labels"),
                                     n, d, m, out["loss"].data_ptr(), out["grad_w1"].data_ptr(),
                                     out["grad_b1"].data_ptr(), out["grad_w2"].data_ptr(), out["grad_b2"].data_ptr(),
-                                    _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
+                                    int(delta_terms), _ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
+                                    _stream(stream))
     _check("arrol_score_mlp_grad", rc)
     return out
 

@@ -53,6 +53,7 @@ struct MlpArgs {
     // delta mode
     const float* resid;          // [n_rows] r_i = (q_i - y_i) / N
     uint16_t* delta_t;           // [m][delta_stride] bf16
+    uint16_t* delta_lo;          // NULL, or [m][delta_stride] bf16: bf16(delta - float(delta_t)), the second term
     int64_t delta_stride;
     float* unit_partial;         // [gridDim.x][2][m]: sums over the workgroup's rollouts for dL/dw2, dL/db1
     // wgrad mode: blockIdx.y = K split, blockIdx.z = group of 256 A rows
@@ -275,7 +276,11 @@ __global__ __launch_bounds__(kThreads) void score_mlp_kernel(MlpArgs a) {
                                 const float dl = pre > 0.f ? resid[j] * w : 0.f;
                                 gw = fmaf(resid[j], fmaxf(pre, 0.f), gw);
                                 gb += dl;
-                                if (live) drow[j * 32] = f32_to_bf16_rne(dl);
+                                if (live) {
+                                    const uint16_t hi = f32_to_bf16_rne(dl);
+                                    drow[j * 32] = hi;
+                                    if (a.delta_lo) (a.delta_lo + (drow - a.delta_t))[j * 32] = f32_to_bf16_rne(dl - bf16_lo(hi));
+                                }
                                 acc[c][j][v] = 0.f;
                             }
                             // sum over the 32 rollout lanes of this half-wave (both halves run the same steps)
@@ -576,7 +581,7 @@ __global__ void mlp_residual_finish_kernel(const float* __restrict__ block_sums,
 }
 
 // delta^T and the per-unit sums from the kept activations: one workgroup per unit u streams its row
-//   delta^T[u][i] = r_i w2_u [a_ui > 0] (bf16, 0 for n_rows <= i < n_pad),
+//   delta^T[u][i] = r_i w2_u [a_ui > 0] (bf16, 0 for n_rows <= i < n_pad; optionally the bf16 remainder too),
 //   dL/dw2_u = sum_i r_i a_ui,  dL/db1_u = sum_i r_i w2_u [a_ui > 0],
 // each lane over its own columns in ascending order, then lanes, then wavefronts: a fixed summation order.
 constexpr int kDeltaThreads = 1024;
@@ -584,6 +589,7 @@ __global__ __launch_bounds__(kDeltaThreads) void mlp_delta_kernel(const float* _
                                                                   const float* __restrict__ resid,
                                                                   const float* __restrict__ w2, int n_rows, int n_pad,
                                                                   uint16_t* __restrict__ delta_t,
+                                                                  uint16_t* __restrict__ delta_lo,
                                                                   float* __restrict__ grad_w2,
                                                                   float* __restrict__ grad_b1) {
     __shared__ float red[2][kDeltaThreads / ARROL_WAVE];
@@ -604,18 +610,24 @@ __global__ __launch_bounds__(kDeltaThreads) void mlp_delta_kernel(const float* _
             for (int q = 0; q < 4; ++q)
                 if (i + q < n_rows) { av[q] = arow[i + q]; rv[q] = resid[i + q]; }
         }
-        uint16_t dq[4];
+        uint16_t dq[4], lq[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const float dl = av[q] > 0.f ? rv[q] * wu : 0.f;
             gw = fmaf(rv[q], av[q], gw);
             gb += dl;
             dq[q] = f32_to_bf16_rne(dl);
+            lq[q] = f32_to_bf16_rne(dl - bf16_lo(dq[q]));
         }
         uint2 o;
         o.x = static_cast<uint32_t>(dq[0]) | (static_cast<uint32_t>(dq[1]) << 16);
         o.y = static_cast<uint32_t>(dq[2]) | (static_cast<uint32_t>(dq[3]) << 16);
         *reinterpret_cast<uint2*>(drow + i) = o;
+        if (delta_lo) {     // second term of the two-term form: what bf16 rounding left of delta
+            o.x = static_cast<uint32_t>(lq[0]) | (static_cast<uint32_t>(lq[1]) << 16);
+            o.y = static_cast<uint32_t>(lq[2]) | (static_cast<uint32_t>(lq[3]) << 16);
+            *reinterpret_cast<uint2*>(delta_lo + static_cast<int64_t>(u) * n_pad + i) = o;
+        }
     }
     gw = wave_sum_f32(gw);
     gb = wave_sum_f32(gb);
@@ -665,18 +677,20 @@ __global__ __launch_bounds__(256) void mlp_transpose_kernel(const uint16_t* __re
 
 struct GradPlan {
     int n_rb, n_pad, n_cb, n_groups, n_kc, splits, kc_per_split;
-    int r_cb, r_vt, r_splits, r_k64_per_split;
+    int r_cb, r_vt, r_gt, r_splits, r_k64_per_split;
     size_t off_score, off_prob, off_resid, off_bsum, off_ht, off_dt, off_unit, off_slab, off_small, off_rslab, off_act, total;
 };
 
 size_t align256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
 
-GradPlan make_grad_plan(int n_rows, int d, int m) {
+GradPlan make_grad_plan(int n_rows, int d, int m, int terms) {
     GradPlan p;
     p.n_rb = (n_rows + BR - 1) / BR;
     p.n_pad = p.n_rb * BR;
     p.n_cb = (d + BR - 1) / BR;              // wgrad: 128 columns of dL/dW1 per workgroup
-    p.n_groups = (m + BU - 1) / BU;
+    // dL/dW1 contracts [hi; lo] (terms * m rows) with H and leaves one partial per term and K split
+    const int mt = terms * m;
+    p.n_groups = (mt + BU - 1) / BU;
     p.n_kc = p.n_pad / BK;
     // split K so that about 256 workgroups run, each with at least 8 chunks; at most 8 partial slabs
     int s = 256 / (p.n_cb * p.n_groups);
@@ -691,11 +705,11 @@ GradPlan make_grad_plan(int n_rows, int d, int m) {
     p.off_resid = o; o = align256(o + sizeof(float) * n_rows);
     p.off_bsum = o;  o = align256(o + sizeof(float) * 2 * ((n_rows + 1023) / 1024));
     p.off_ht = o;    o = align256(o + sizeof(uint16_t) * static_cast<size_t>(d) * p.n_pad);
-    p.off_dt = o;    o = align256(o + sizeof(uint16_t) * static_cast<size_t>(m) * p.n_pad);
+    p.off_dt = o;    o = align256(o + sizeof(uint16_t) * static_cast<size_t>(mt) * p.n_pad);
     // per-unit partial sums of the tile kernel: one row per 128 rollouts
     p.off_unit = o;  o = align256(o + sizeof(float) * static_cast<size_t>(p.n_rb) * 2 * m);
     p.off_slab = o;
-    if (p.splits > 1) o = align256(o + sizeof(float) * static_cast<size_t>(p.splits) * m * d);
+    if (p.splits * terms > 1) o = align256(o + sizeof(float) * static_cast<size_t>(p.splits) * mt * d);
     p.off_small = o;                      // partial scores of the small-batch / ring forward pass
     if (d % 64 == 0) {
         const size_t blocks = n_rows <= kSmallMaxRows ? (m + 31) / 32 : (m + 255) / 256;
@@ -703,15 +717,16 @@ GradPlan make_grad_plan(int n_rows, int d, int m) {
     }
     // ring wgrad: 256-column blocks; K split so that about 256 workgroups run, at most 8 partial slabs
     p.r_cb = (d + 255) / 256;
-    p.r_vt = (m + 255) / 256;
-    int rs = 256 / (p.r_cb * p.r_vt);
+    p.r_vt = (m + 255) / 256;          // forward pass
+    p.r_gt = (mt + 255) / 256;         // dL/dW1
+    int rs = 256 / (p.r_cb * p.r_gt);
     if (rs > p.n_kc / 8) rs = p.n_kc / 8;
     if (rs > 8) rs = 8;
     if (rs < 1) rs = 1;
     p.r_k64_per_split = (p.n_kc + rs - 1) / rs;
     p.r_splits = (p.n_kc + p.r_k64_per_split - 1) / p.r_k64_per_split;
     p.off_rslab = o;
-    if (d % 64 == 0 && p.r_splits > 1) o = align256(o + sizeof(float) * static_cast<size_t>(p.r_splits) * m * d);
+    if (d % 64 == 0 && p.r_splits * terms > 1) o = align256(o + sizeof(float) * static_cast<size_t>(p.r_splits) * mt * d);
     p.off_act = o;                        // small-batch / ring forward pass: kept activations, fp32 [m][n_pad]
     if (d % 64 == 0) o = align256(o + sizeof(float) * static_cast<size_t>(m) * p.n_pad);
     p.total = o;
@@ -783,17 +798,18 @@ extern "C" int arrol_score_mlp(const void* hidden, int64_t row_stride_elems, con
     return launch_mlp<kForward>(a, dim3((n_rows + BR - 1) / BR), st);
 }
 
-extern "C" size_t arrol_score_mlp_grad_workspace_bytes(int32_t n_rows, int32_t d, int32_t m) {
-    if (n_rows < 1 || d < 8 || m < 1) return 0;
-    return make_grad_plan(n_rows, d, m).total;
+extern "C" size_t arrol_score_mlp_grad_workspace_bytes(int32_t n_rows, int32_t d, int32_t m, int32_t delta_terms) {
+    if (n_rows < 1 || d < 8 || m < 1 || delta_terms < 1 || delta_terms > 2) return 0;
+    return make_grad_plan(n_rows, d, m, delta_terms).total;
 }
 
 extern "C" int arrol_score_mlp_grad(const void* hidden, int64_t row_stride_elems, const int64_t* row_index,
                                     const void* w1, const float* b1, const float* w2, float b2,
                                     const float* labels, int32_t n_rows, int32_t d, int32_t m, float* loss_out,
                                     float* grad_w1, float* grad_b1, float* grad_w2, float* grad_b2,
-                                    void* workspace, size_t workspace_bytes, void* stream) {
+                                    int32_t delta_terms, void* workspace, size_t workspace_bytes, void* stream) {
     if (n_rows < 0 || d < 8 || (d & 7) || m < 1 || row_stride_elems < d || (row_stride_elems & 7)) return ARROL_EINVAL;
+    if (delta_terms < 1 || delta_terms > 2 || m > INT32_MAX / 2) return ARROL_EINVAL;
     if (!grad_w1 || !grad_b1 || !grad_w2) return ARROL_EINVAL;
     if (n_rows == 0) {   // empty batch: zero loss and gradients
         hipStream_t s0 = static_cast<hipStream_t>(stream);
@@ -809,7 +825,8 @@ extern "C" int arrol_score_mlp_grad(const void* hidden, int64_t row_stride_elems
         return arrol_launch_status();
     }
     if (!hidden || !w1 || !w2 || !labels || !arrol_aligned16(hidden) || !arrol_aligned16(w1)) return ARROL_EINVAL;
-    const GradPlan p = make_grad_plan(n_rows, d, m);
+    const GradPlan p = make_grad_plan(n_rows, d, m, delta_terms);
+    const int mt = delta_terms * m;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < p.total) return ARROL_EWORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     unsigned char* ws = static_cast<unsigned char*>(workspace);
@@ -819,7 +836,8 @@ extern "C" int arrol_score_mlp_grad(const void* hidden, int64_t row_stride_elems
     float* bsum = reinterpret_cast<float*>(ws + p.off_bsum);
     const int n_rblocks = (n_rows + 1023) / 1024;
     uint16_t* ht = reinterpret_cast<uint16_t*>(ws + p.off_ht);
-    uint16_t* dt = reinterpret_cast<uint16_t*>(ws + p.off_dt);
+    uint16_t* dt = reinterpret_cast<uint16_t*>(ws + p.off_dt);                       // [hi; lo]: delta_terms * m rows
+    uint16_t* dt_lo = delta_terms == 2 ? dt + static_cast<int64_t>(m) * p.n_pad : nullptr;
     float* unit = reinterpret_cast<float*>(ws + p.off_unit);
     float* slab = reinterpret_cast<float*>(ws + p.off_slab);
 
@@ -863,9 +881,9 @@ extern "C" int arrol_score_mlp_grad(const void* hidden, int64_t row_stride_elems
     // delta^T and the per-unit sums
     if (kept) {
         arrol_launch(mlp_delta_kernel, dim3(m), dim3(kDeltaThreads), 0, st, act, static_cast<int64_t>(p.n_pad), resid, w2,
-                     n_rows, p.n_pad, dt, grad_w2, grad_b1);
+                     n_rows, p.n_pad, dt, dt_lo, grad_w2, grad_b1);
     } else {
-        a.resid = resid; a.delta_t = dt; a.delta_stride = p.n_pad; a.unit_partial = unit;
+        a.resid = resid; a.delta_t = dt; a.delta_lo = dt_lo; a.delta_stride = p.n_pad; a.unit_partial = unit;
         rc = launch_mlp<kDelta>(a, dim3(p.n_rb), st);
         if (rc != ARROL_OK) return rc;
         arrol_launch(reduce_rows_f32_kernel<0>, dim3((m + 31) / 32), dim3(256), 0, st, unit, p.n_rb,
@@ -879,16 +897,18 @@ extern "C" int arrol_score_mlp_grad(const void* hidden, int64_t row_stride_elems
         // dL/dW1 = delta^T . H over the rollouts, the hidden states read in place
         float* rslab = reinterpret_cast<float*>(ws + p.off_rslab);
         MlpRingArgs g = {};
-        g.a = dt; g.a_stride = static_cast<unsigned>(p.n_pad) * 2; g.a_rows = m;
+        // the partials [K split][term][m][d] are delta_terms * r_splits slabs of m * d values
+        const int n_slabs = p.r_splits * delta_terms;
+        g.a = dt; g.a_stride = static_cast<unsigned>(p.n_pad) * 2; g.a_rows = mt;
         g.b = a.hidden; g.b_stride = static_cast<unsigned>(row_stride_elems * 2);
         g.b_rows = d; g.b_k_rows = n_rows;
         g.n_k64 = (n_rows + 63) / 64; g.k64_per_split = p.r_k64_per_split;
-        g.c_out = p.r_splits > 1 ? rslab : grad_w1; g.c_stride = d;
-        rc = launch_mlp_ring<kWgrad>(g, dim3(p.r_cb, p.r_vt, p.r_splits), st);
+        g.c_out = n_slabs > 1 ? rslab : grad_w1; g.c_stride = d;
+        rc = launch_mlp_ring<kWgrad>(g, dim3(p.r_cb, p.r_gt, p.r_splits), st);
         if (rc != ARROL_OK) return rc;
-        if (p.r_splits > 1)
+        if (n_slabs > 1)
             arrol_launch(reduce_rows_f32_kernel<0>, dim3(static_cast<unsigned>((width + 31) / 32)), dim3(256), 0, st,
-                         rslab, p.r_splits, width, width, 1.f, grad_w1);
+                         rslab, n_slabs, width, width, 1.f, grad_w1);
         return arrol_launch_status();
     }
     // gathered rows or d not a multiple of 64: H^T, then the tile kernel
@@ -897,12 +917,13 @@ extern "C" int arrol_score_mlp_grad(const void* hidden, int64_t row_stride_elems
     MlpArgs g = {};
     g.hidden = ht; g.row_stride = p.n_pad; g.row_index = nullptr;
     g.w1 = dt; g.a_stride = p.n_pad;
-    g.n_rows = d; g.d = p.n_pad; g.m = m;
-    g.c_out = p.splits > 1 ? slab : grad_w1; g.c_stride = d; g.kc_per_split = p.kc_per_split;
+    const int n_slabs = p.splits * delta_terms;
+    g.n_rows = d; g.d = p.n_pad; g.m = mt;
+    g.c_out = n_slabs > 1 ? slab : grad_w1; g.c_stride = d; g.kc_per_split = p.kc_per_split;
     rc = launch_mlp<kWgrad>(g, dim3(p.n_cb, p.splits, p.n_groups), st);
     if (rc != ARROL_OK) return rc;
-    if (p.splits > 1)
+    if (n_slabs > 1)
         arrol_launch(reduce_rows_f32_kernel<0>, dim3(static_cast<unsigned>((width + 31) / 32)), dim3(256), 0, st,
-                     slab, p.splits, width, width, 1.f, grad_w1);
+                     slab, n_slabs, width, width, 1.f, grad_w1);
     return arrol_launch_status();
 }

@@ -134,15 +134,19 @@ def test_bad_arguments_are_rejected_on_the_host(pkg):
     assert L.arrol_adamw_step(fake, None, fake, fake, 8, 1, 1e-3, 0.9, 0.999, 1e-8, 0.0, None, None) == -1
     assert L.arrol_adamw_step(None, None, None, None, 0, 1, 1e-3, 0.9, 0.999, 1e-8, 0.0, None, None) == 0
     # MLP head gradient: bad d, m < 1, missing outputs, workspace missing / short / misaligned
-    mg = lambda d, m, gw1, ws, nbytes: L.arrol_score_mlp_grad(fake, 16, None, fake, None, fake, 0.0, fake, 4, d, m, None,
-                                                               gw1, fake, fake, None, ws, nbytes, None)
+    mg = lambda d, m, gw1, ws, nbytes, terms=1: L.arrol_score_mlp_grad(fake, 16, None, fake, None, fake, 0.0, fake, 4, d, m, None,
+                                                                        gw1, fake, fake, None, terms, ws, nbytes, None)
     assert mg(12, 8, fake, fake, 1 << 24) == -1
     assert mg(16, 0, fake, fake, 1 << 24) == -1
     assert mg(16, 8, None, fake, 1 << 24) == -1
     assert mg(16, 8, fake, None, 0) == -2
     assert mg(16, 8, fake, fake, 256) == -2
     assert mg(16, 8, fake, ctypes.c_void_p(0x1010), 1 << 24) == -2
-    assert L.arrol_score_mlp_grad_workspace_bytes(4, 16, 8) >= 3 * 4 * 4 + 128 * (16 + 8) * 2
+    assert mg(16, 8, fake, fake, 1 << 24, terms=0) == -1 and mg(16, 8, fake, fake, 1 << 24, terms=3) == -1
+    assert L.arrol_score_mlp_grad_workspace_bytes(4, 16, 8, 1) >= 3 * 4 * 4 + 128 * (16 + 8) * 2
+    # the two-term form holds a second delta^T and a second partial of dL/dW1
+    assert L.arrol_score_mlp_grad_workspace_bytes(4, 16, 8, 2) >= L.arrol_score_mlp_grad_workspace_bytes(4, 16, 8, 1) + 128 * 8 * 2 + 8 * 16 * 4
+    assert L.arrol_score_mlp_grad_workspace_bytes(4, 16, 8, 0) == 0 and L.arrol_score_mlp_grad_workspace_bytes(4, 16, 8, 3) == 0
     # trace confidence: bad d / V, null lse, workspace; aggregates: window < 1, percent outside [1, 100]
     assert L.arrol_token_confidence(fake, fake, fake, 4, 100, 12, fake, fake, 1 << 20, None) == -1
     assert L.arrol_token_confidence(fake, fake, fake, 4, 0, 16, fake, fake, 1 << 20, None) == -1

@@ -153,8 +153,8 @@ def mlp_case(n, d, m, seed):
     return hidden, w1, b1, w2, labels
 
 
-def check_mlp_grad(A, hidden, w1, b1, w2, b2, labels, row_index=None):
-    out = A.arrol_score_mlp_grad(hidden, w1, b1, w2, b2, labels, row_index=row_index)
+def check_mlp_grad(A, hidden, w1, b1, w2, b2, labels, row_index=None, delta_terms=1):
+    out = A.arrol_score_mlp_grad(hidden, w1, b1, w2, b2, labels, row_index=row_index, delta_terms=delta_terms)
     torch.cuda.synchronize()
     hb = bits(hidden)
     if row_index is not None:
@@ -181,13 +181,15 @@ def check_mlp_grad(A, hidden, w1, b1, w2, b2, labels, row_index=None):
     act = np.maximum(pre, 0.0)
     tol_w2 = F32 * (np.abs(r)[:, None] * act).sum(axis=0) + 1e-9 * act.mean(axis=0) + 1e-12
     assert np.all(np.abs(npy(out["grad_w2"]) - gw2_o) <= tol_w2)
-    # dL/dW1: delta is rounded to bf16 (unit roundoff 2^-8, worst case summed), fp32 accumulation on top
-    bound = (2.0 ** -8 + F32) * (delta.T @ np.abs(H)) + flip.T @ np.abs(H) + 1e-12
+    # dL/dW1: delta is rounded to bf16 (unit roundoff 2^-8, worst case summed; 2^-16 for the two-term form),
+    # fp32 accumulation on top
+    unit = 2.0 ** -8 if delta_terms == 1 else 2.0 ** -16
+    bound = (unit + F32) * (delta.T @ np.abs(H)) + flip.T @ np.abs(H) + 1e-12
     err = np.abs(npy(out["grad_w1"]).astype(np.float64) - gW1_o)
     assert np.all(err <= bound), float((err / bound).max())
     # rounding errors average out: the error as a whole is far below the worst case
     if not near.any() and np.linalg.norm(gW1_o) > 0:
-        assert np.linalg.norm(err) <= 2.0 ** -8 * np.linalg.norm(gW1_o)
+        assert np.linalg.norm(err) <= (2.0 ** -8 if delta_terms == 1 else 1e-5) * np.linalg.norm(gW1_o)
     return out
 
 
@@ -199,6 +201,36 @@ def test_score_mlp_grad_matches_oracle(A, n, d, m):
     print("[case] score_mlp_grad n=%d d=%d m=%d" % (n, d, m), flush=True)
     hidden, w1, b1, w2, labels = mlp_case(n, d, m, seed=n + d + m)
     check_mlp_grad(A, hidden, w1, b1, w2 * 4.0, -0.125, labels)
+
+
+@pytest.mark.parametrize("n,d,m", [(130, 264, 100),      # tile kernels (d not a multiple of 64)
+                                   (300, 1024, 257),     # wavefront-per-block forward, in-place dL/dW1, one K split
+                                   (512, 2048, 512),
+                                   (2048, 256, 128),     # several K splits
+                                   (4500, 128, 300)])    # ring-pipeline forward
+def test_score_mlp_grad_two_term_delta_is_fp32_accurate(A, n, d, m):
+    """delta_terms = 2: dL/dW1 within 1e-5 of the float64 oracle in norm (2^-8 for the one-term form), and
+    strictly closer than the one-term result; everything else unchanged bit for bit."""
+    print("[case] score_mlp_grad two-term n=%d d=%d m=%d" % (n, d, m), flush=True)
+    hidden, w1, b1, w2, labels = mlp_case(n, d, m, seed=3 * n + d + m)
+    o2 = check_mlp_grad(A, hidden, w1, b1, w2 * 4.0, -0.125, labels, delta_terms=2)
+    o1 = A.arrol_score_mlp_grad(hidden, w1, b1, w2 * 4.0, -0.125, labels)
+    torch.cuda.synchronize()
+    for k in ("loss", "grad_b1", "grad_w2", "grad_b2"):
+        assert torch.equal(o1[k], o2[k]), k
+    _, gW1_o, _, _, _ = O.score_mlp_ce_grad(bits(hidden), bits(w1), npy(b1), npy(w2 * 4.0), np.float32(-0.125), npy(labels))
+    e1 = np.linalg.norm(npy(o1["grad_w1"]).astype(np.float64) - gW1_o)
+    e2 = np.linalg.norm(npy(o2["grad_w1"]).astype(np.float64) - gW1_o)
+    assert e2 < 0.05 * e1, (e1, e2)
+
+
+def test_score_mlp_grad_two_term_delta_gathered_rows(A):
+    print("[case] score_mlp_grad two-term gathered", flush=True)
+    hidden, w1, b1, w2, _ = mlp_case(200, 128, 96, seed=5)
+    g = torch.Generator(device=DEV); g.manual_seed(8)
+    idx = torch.randint(0, 200, (150,), generator=g, device=DEV, dtype=torch.int64)
+    soft = torch.rand(150, generator=g, device=DEV)
+    check_mlp_grad(A, hidden, w1, b1, w2, 0.0, soft, row_index=idx, delta_terms=2)
 
 
 def test_score_mlp_grad_gathered_rows_no_bias_dead_units_and_empty_batch(A):
