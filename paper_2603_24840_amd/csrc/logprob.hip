@@ -26,6 +26,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kNegBig = -1.0e30f;  // finite stand-in for "no logit seen yet"
@@ -72,7 +73,7 @@ struct LaneState {
 // Folds one finished accumulator tile into the running (max, sumexp, target logit) and clears it.
 // acc[i][j][v] is the logit of vocab row vrow0 + i*32 + (v/4)*8 + lh*4 + v%4 for the lane's token of
 // block j (MFMA 32x32 result layout); WROWS = vocab rows per wave tile.
-template <int TM, int TN, int WROWS, bool CLEAR = true>
+template <int TM, int TN, int WROWS>
 __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[TM][TN], LaneState<TN>& st, int vrow0, int V, int lh) {
     if (vrow0 + WROWS > V) {  // tile hangs over the end of the vocabulary
 #pragma unroll
@@ -109,7 +110,7 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[TM][TN], LaneState<T
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 sum += __builtin_amdgcn_exp2f(fmaf(acc[i][j][v], kLog2e, neg));
-                if (CLEAR) acc[i][j][v] = 0.f;
+                acc[i][j][v] = 0.f;
             }
         // difference first: exactly 0 when the maximum did not move (also for the -1e30 sentinel)
         st.run_s[j] = st.run_s[j] * __builtin_amdgcn_exp2f((st.run_m[j] - m_new) * kLog2e) + sum;
@@ -138,6 +139,107 @@ __device__ __forceinline__ void write_partials(LaneState<TN>& st, float* red, in
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int col = wn * (BN / WN) + j * 32 + l31;
+            red[(wm * 3 + 0) * BN + col] = st.run_m[j];
+            red[(wm * 3 + 1) * BN + col] = st.run_s[j];
+            red[(wm * 3 + 2) * BN + col] = st.tgt_z[j];
+        }
+    }
+    __syncthreads();
+    for (int col = tid; col < BN; col += NT) {
+        const int64_t t = tok0 + col;
+        if (t >= T) continue;
+        float m = red[col], s = red[BN + col], z = red[2 * BN + col];
+#pragma unroll
+        for (int w = 1; w < WM; ++w) {
+            const float om = red[(w * 3 + 0) * BN + col], os = red[(w * 3 + 1) * BN + col];
+            const float mm = fmaxf(m, om);
+            s = s * __builtin_amdgcn_exp2f((m - mm) * kLog2e) + os * __builtin_amdgcn_exp2f((om - mm) * kLog2e);
+            m = mm;
+            z += red[(w * 3 + 2) * BN + col];
+        }
+        float* p = part + static_cast<int64_t>(sp) * 3 * T + t;
+        p[0] = m;
+        p[T] = s;
+        p[2 * T] = z;
+    }
+}
+
+// The same for the 16x16x32 MFMA result layout: acc[i][j][v] is the logit of vocab row vrow0 + i*16 + lq*4 + v
+// (lq = lane / 16) for the lane's token of block j (token j*16 + lane%16 of the wave's range).  The accumulators
+// are left as they are (the next tile's first MFMAs take 0 as their addend).
+template <int TI, int TJ, int WROWS>
+__device__ __forceinline__ void tile_epilogue16(f32x4 (&acc)[TI][TJ], LaneState<TJ>& st, int vrow0, int V, int lq,
+                                                const int32_t* tgt_wave, int tgt_valid, int l15) {
+    // the lane's targets are fetched again for every tile (from cache) instead of living in registers through
+    // the K loop: tgt_wave (wave-uniform) points at the wave's first token, of which tgt_valid exist
+    int tgt[TJ];
+#pragma unroll
+    for (int j = 0; j < TJ; ++j) tgt[j] = j * 16 + l15 < tgt_valid ? tgt_wave[j * 16 + l15] : -1;
+    if (vrow0 + WROWS > V) {  // tile hangs over the end of the vocabulary
+        const int lim = V - vrow0 - lq * 4;   // rows of this lane from here on are past the end: one value per tile,
+#pragma unroll                                // compared with constants (nothing per (i, v) to keep in registers)
+        for (int i = 0; i < TI; ++i)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const bool dead = i * 16 + v >= lim;
+#pragma unroll
+                for (int j = 0; j < TJ; ++j) acc[i][j][v] = dead ? -INFINITY : acc[i][j][v];
+            }
+    }
+#pragma unroll
+    for (int j = 0; j < TJ; ++j) {
+        const int rel = tgt[j] - vrow0;
+        const bool mine = rel >= 0 && rel < WROWS && ((rel >> 2) & 3) == lq;
+        if (__any(mine)) {
+            const int code = mine ? ((rel >> 4) * 4 + (rel & 3)) : -1;
+#pragma unroll
+            for (int i = 0; i < TI; ++i)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (code == i * 4 + v) st.tgt_z[j] = acc[i][j][v];
+        }
+        float mx = acc[0][j][0];
+#pragma unroll
+        for (int i = 0; i < TI; ++i)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) mx = fmaxf(mx, acc[i][j][v]);
+        const float m_new = fmaxf(st.run_m[j], mx);
+        const float neg = -m_new * kLog2e;
+        float sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < TI; ++i)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) sum += __builtin_amdgcn_exp2f(fmaf(acc[i][j][v], kLog2e, neg));
+        // difference first: exactly 0 when the maximum did not move (also for the -1e30 sentinel)
+        st.run_s[j] = st.run_s[j] * __builtin_amdgcn_exp2f((st.run_m[j] - m_new) * kLog2e) + sum;
+        st.run_m[j] = m_new;
+        __builtin_amdgcn_sched_barrier(0);   // one token column at a time: keeps the temporaries of the exp chains few
+    }
+}
+
+// End of a workgroup's vocabulary range, 16x16 layout: merge the four lane quarters (same token, different
+// vocab rows), then the WM waves that share a token range through LDS, and write the partial of split sp.
+template <int TJ, int WM, int WN, int BN, int NT>
+__device__ __forceinline__ void write_partials16(LaneState<TJ>& st, float* red, int wm, int wn, int l15, int lq,
+                                                 int tid, int64_t tok0, int64_t T, int sp, float* part) {
+#pragma unroll
+    for (int j = 0; j < TJ; ++j) {
+#pragma unroll
+        for (int msk = 16; msk <= 32; msk <<= 1) {
+            const float om = __shfl_xor(st.run_m[j], msk, ARROL_WAVE);
+            const float os = __shfl_xor(st.run_s[j], msk, ARROL_WAVE);
+            const float oz = __shfl_xor(st.tgt_z[j], msk, ARROL_WAVE);
+            const float m = fmaxf(st.run_m[j], om);
+            st.run_s[j] = st.run_s[j] * __builtin_amdgcn_exp2f((st.run_m[j] - m) * kLog2e) +
+                          os * __builtin_amdgcn_exp2f((om - m) * kLog2e);
+            st.run_m[j] = m;
+            st.tgt_z[j] += oz;
+        }
+    }
+    if (lq == 0) {
+#pragma unroll
+        for (int j = 0; j < TJ; ++j) {
+            const int col = wn * (BN / WN) + j * 16 + l15;
             red[(wm * 3 + 0) * BN + col] = st.run_m[j];
             red[(wm * 3 + 1) * BN + col] = st.run_s[j];
             red[(wm * 3 + 2) * BN + col] = st.tgt_z[j];
@@ -291,28 +393,31 @@ __global__ __launch_bounds__(C::NT) void logprob_kernel(LogprobArgs a) {
 
 // ---------------------------------------------------------------------------------------------
 // Fast kernel (d a multiple of 64): global -> LDS directly (no staging registers) into a ring of
-// RING K32 slots (32 k-values = 64 bytes of each of the BM + BN tile rows).
+// RING K32 slots (32 k-values = 64 bytes of each of the BM + BN tile rows); the contraction runs on
+// v_mfma_f32_16x16x32_bf16, one whole K32 slot per instruction: 8 x 4 blocks of 16 vocabulary rows x 16 tokens
+// per wave.  (In a register-only loop on random operands this shape sustains 2.0 PFLOP/s under the part's
+// power limit, the 32x32x16 shape 1.8; the kernel as a whole gains 2-3 % on the workloads' data.)
 //
 // Loads always fetch whole 128-byte lines of a row, i.e. the two K32 halves that go to two
 // consecutive slots (a "pair").  The L1 path moves 64 bytes per clock, so a pair costs as many L1
 // cycles as half of its MFMA time; to keep that evenly spread, the W lines ("A") of a pair are
-// requested during one K32 iteration and its H lines ("B") during the next.  The pipeline per
-// iteration i (chunk i lives in slot i % RING):
-//   K16 step 0: MFMAs on fragments already in registers; between them the step-1 fragment reads of
-//               slot i and two of this iteration's four load instructions;
-//   K16 step 1: MFMAs; between them the step-0 reads of the W fragments of slot i+1 (certified one
-//               barrier earlier), then - four MFMAs before the end - the wait for this wave's older
-//               loads and the workgroup barrier, then the step-0 reads of the H fragments of slot i+1
-//               and the remaining loads.  The last MFMAs cover the latency of those reads, so the
-//               matrix pipe never waits for an LDS round trip behind a barrier.
-// The barrier inside iteration i certifies the W part of slot i+2 and the H part of slot i+1 and
-// releases slot i-1 (W lines) / slot i-2.. for refilling; see the table in the loop for who loads what.
-// The first K16 step of every vocabulary tile takes the constant 0 as its MFMA addend, so the epilogue
-// never clears the accumulators.
-// (ring_nt.h holds the same pipeline in a general form - row strides, K ranges, an epilogue callback - for
-// the MLP head's kernels, which walk one tile per workgroup.  This kernel walks many tiles with the epilogue
-// between them and keeps its own instance: built on the general form it ran 7 % slower, the compiler then
-// spilling scalar registers inside the loop.)
+// requested during one K32 iteration and its H lines ("B") during the next, all four load instructions of an
+// iteration in its first half.  The pipeline per iteration i (chunk i lives in slot i % RING, its fragments
+// are in registers when the iteration starts):
+//   rows 0-3 of MFMAs (a row = one vocabulary block x the 4 token blocks); W fragment r of slot i+1 is read
+//               into the registers of W fragment r as soon as row r has been issued (the W part of slot i+1
+//               was certified one barrier earlier);
+//   the wait for this wave's older loads, the workgroup barrier;
+//   the H fragments of slot i+1 (certified just now) into the second H fragment set, then rows 4-7 with the
+//               remaining W fragment reads between them: four rows of MFMAs cover the eight waves' reads
+//               queueing on the LDS, so the matrix pipe never waits for an LDS round trip behind a barrier.
+// The barrier inside iteration i certifies the W part of slot i+2 and the H part of slot i+1; every read of
+// slot i has completed by then (they were issued during iteration i-1 and at the start of iteration i), so
+// slot i is free for refilling from there on.
+// The first chunk of every vocabulary tile takes the constant 0 as its MFMA addend, so the epilogue never
+// clears the accumulators.
+// (ring_nt.h holds the 32x32x16 form of this pipeline in a general form - row strides, K ranges, an epilogue
+// after the walk - for the MLP head's kernels, which walk one tile per workgroup.)
 // ---------------------------------------------------------------------------------------------
 template <int BM_, int BN_, int WM_, int WN_>
 struct RingTile {
@@ -327,7 +432,7 @@ struct RingTile {
     static constexpr int LOADS = 2 * G;                     // load instructions per wave and iteration
     static_assert(BM == BN, "W and H tiles are loaded by the same code in alternate iterations");
     static_assert(BM % (16 * NW) == 0, "whole 16-row load groups per wave");
-    static_assert(LOADS == 4 && TM * TN == 8 && TM + TN <= 8, "the hand-placed schedule below");
+    static_assert(LOADS == 4, "the hand-placed schedule below");
 };
 
 template <int N>
@@ -338,7 +443,8 @@ __device__ __forceinline__ void wait_vmcnt() {  // s_waitcnt vmcnt(N) only (gfx9
 template <class C>
 __global__ __launch_bounds__(C::NT) void logprob_ring_kernel(LogprobArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    constexpr int BM = C::BM, BN = C::BN, TM = C::TM, TN = C::TN, RING = C::RING;
+    constexpr int BM = C::BM, BN = C::BN, RING = C::RING;
+    constexpr int TI = BM / C::WM / 16, TJ = BN / C::WN / 16;   // 16 x 16 blocks per wave: vocabulary x tokens
     typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
     int tb, sp, vt_lo, vt_hi;
@@ -347,14 +453,15 @@ __global__ __launch_bounds__(C::NT) void logprob_ring_kernel(LogprobArgs a) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / C::WN, wn = wave % C::WN;
-    const int l31 = lane & 31, lh = lane >> 5;
+    const int l15 = lane & 15, lq = lane >> 4;
     const int64_t tok0 = static_cast<int64_t>(tb) * BN;
     const int n_k64 = a.d / 64;
 
     // ---- loader geometry: one instruction moves 16 rows x 64 bytes; lane -> (row lane/4, physical
-    //      16-byte position lane%4), which holds logical chunk (lane%4) ^ ((row/4)%4) -----------
+    //      16-byte position lane%4), which holds logical chunk (lane%4) ^ g(row), g(row) = 2 * ((row/4)%2)
+    //      (see the fragment reads) -----------
     const int ld_row = lane >> 2;
-    const int ld_kb = ((lane & 3) ^ ((lane >> 4) & 3)) * 16;   // byte offset inside the K32 half
+    const int ld_kb = ((lane & 3) ^ (((lane >> 4) & 1) << 1)) * 16;   // byte offset inside the K32 half
     // Addresses are (wave-uniform 64-bit base in SGPRs) + (per-lane 32-bit byte offset): the base
     // carries tile and K position, the lane offset the row inside the tile (clamped at the end of the
     // vocabulary / token range, so every load stays inside W and H) and the swizzled chunk.
@@ -362,22 +469,22 @@ __global__ __launch_bounds__(C::NT) void logprob_ring_kernel(LogprobArgs a) {
     const int64_t tile_bytes = BM * row_bytes;
     unsigned a_voff[C::G], b_voff[C::G];
     {
-        const int64_t rows_valid = a.T - tok0 < BN ? a.T - tok0 : BN;
+        const int rows_valid = static_cast<int>(a.T - tok0 < BN ? a.T - tok0 : BN);
 #pragma unroll
         for (int g = 0; g < C::G; ++g) {
-            int64_t r = (wave * C::G + g) * 16 + ld_row;
+            int r = (wave * C::G + g) * 16 + ld_row;
             r = r < rows_valid ? r : rows_valid - 1;
-            b_voff[g] = static_cast<unsigned>(r * row_bytes + ld_kb);
+            b_voff[g] = static_cast<unsigned>(r) * static_cast<unsigned>(row_bytes) + ld_kb;   // < 256 rows x 16 KiB
         }
     }
     auto point_at_tile = [&](int vt) {
-        const int64_t left = static_cast<int64_t>(a.V) - static_cast<int64_t>(vt) * BM;
-        const int64_t rows_valid = left < BM ? (left > 0 ? left : 1) : BM;   // left <= 0 only past the last pair
+        const int left = a.V - vt * BM;                                      // vt * BM < V + BM: no overflow
+        const int rows_valid = left < BM ? (left > 0 ? left : 1) : BM;       // left <= 0 only past the last pair
 #pragma unroll
         for (int g = 0; g < C::G; ++g) {
-            int64_t r = (wave * C::G + g) * 16 + ld_row;
+            int r = (wave * C::G + g) * 16 + ld_row;
             r = r < rows_valid ? r : rows_valid - 1;
-            a_voff[g] = static_cast<unsigned>(r * row_bytes + ld_kb);
+            a_voff[g] = static_cast<unsigned>(r) * static_cast<unsigned>(row_bytes) + ld_kb;
         }
     };
     // two load streams, each walking the pairs (pair = two K32 slots = one 128-byte line per row) of the
@@ -436,41 +543,38 @@ __global__ __launch_bounds__(C::NT) void logprob_ring_kernel(LogprobArgs a) {
     constexpr std::false_type kA{};   // W lines
     constexpr std::true_type kB{};    // H lines
 
-    LaneState<TN> st;
+    LaneState<TJ> st;
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
+    for (int j = 0; j < TJ; ++j) {
         st.run_m[j] = kNegBig; st.run_s[j] = 0.f; st.tgt_z[j] = 0.f;
-        const int64_t t = tok0 + wn * (BN / C::WN) + j * 32 + l31;
-        st.tgt[j] = t < a.T ? a.targets[t] : -1;
     }
-    f32x16 acc[TM][TN];
+    // tokens of this wave: tok_wave + 0 .. 63; the first tgt_valid of them exist (both wave-uniform)
+    const int64_t tok_wave = tok0 + wn * (BN / C::WN);
+    const int32_t* tgt_wave = a.targets + (tok_wave < a.T ? tok_wave : 0);
+    const int tgt_valid = tok_wave < a.T ? static_cast<int>(a.T - tok_wave < BN / C::WN ? a.T - tok_wave : BN / C::WN) : 0;
+    f32x4 acc[TI][TJ];
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TI; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+        for (int j = 0; j < TJ; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+            for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.f;
 
-    // fragment reads: row (wave base + i*32 + l31) of a slot, 16-byte chunk kk*2 + lh, swizzled
-    const int swz = (l31 >> 2) & 3;
-    const int a_off0 = (wm * (BM / C::WM) + l31) * 64 + ((lh ^ swz) << 4);          // K16 step 0
-    const int a_off1 = (wm * (BM / C::WM) + l31) * 64 + (((2 + lh) ^ swz) << 4);    // K16 step 1
-    const int b_off0 = BM * 64 + (wn * (BN / C::WN) + l31) * 64 + ((lh ^ swz) << 4);
-    const int b_off1 = BM * 64 + (wn * (BN / C::WN) + l31) * 64 + (((2 + lh) ^ swz) << 4);
-    bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];   // fragments of K16 step 0 / step 1
-    auto read_a = [&](bf16x8 (&fa)[TM], const unsigned char* base, int off, int m) {
-        fa[m] = *reinterpret_cast<const bf16x8*>(base + off + m * 32 * 64);
+    // fragment reads: one MFMA takes the whole K32 of a slot: row (wave base + i*16 + lane%16), 16-byte chunk
+    // lane/16 at position chunk ^ g(row).  Measured on the device: a 128-bit LDS read serves per cycle the 16
+    // lanes that share lane bit 5 and the parity of lane bits 2, 3, 4, so two lanes of a half-wave that fall on
+    // the same 16-byte bank group must differ in an odd number of those bits.  Here the bank group is
+    // (row%4, position) = (l1 l0, l5 ^ l2, l4): the two lanes of a half-wave that share one differ in l3 alone.
+    // (The 32x32 kernel's swizzle (row/4)%4 makes them differ in l2 and l4: two-way conflicts on every read.)
+    const int swz = ((l15 >> 2) & 1) << 1;
+    const int a_off = (wm * (BM / C::WM) + l15) * 64 + ((lq ^ swz) << 4);
+    const int b_off = BM * 64 + (wn * (BN / C::WN) + l15) * 64 + ((lq ^ swz) << 4);
+    bf16x8 fa[TI], fbe[TJ], fbo[TJ];   // W fragments (reloaded row by row), H fragments of even / odd iterations
+    auto read_a = [&](const unsigned char* base, int i) {
+        fa[i] = *reinterpret_cast<const bf16x8*>(base + a_off + i * 16 * 64);
     };
-    auto read_b = [&](bf16x8 (&fb)[TN], const unsigned char* base, int off, int j) {
-        fb[j] = *reinterpret_cast<const bf16x8*>(base + off + j * 32 * 64);
-    };
-    auto mma = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], int x) {
-        acc[x / TN][x % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[x / TN], fb[x % TN], acc[x / TN][x % TN], 0, 0, 0);
-    };
-    // first K16 step of a tile: the addend is the constant 0, so the accumulators never have to be cleared
-    auto mma0 = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], int x) {
-        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        acc[x / TN][x % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[x / TN], fb[x % TN], zero, 0, 0, 0);
+    auto read_b = [&](bf16x8 (&fb)[TJ], const unsigned char* base, int j) {
+        fb[j] = *reinterpret_cast<const bf16x8*>(base + b_off + j * 16 * 64);
     };
 
     // Load schedule (pair p = chunks 2p, 2p+1 -> slots 2p % RING, (2p+1) % RING):
@@ -483,58 +587,79 @@ __global__ __launch_bounds__(C::NT) void logprob_ring_kernel(LogprobArgs a) {
     wait_vmcnt<C::LOADS>();
     __syncthreads();
 #pragma unroll
-    for (int j = 0; j < TN; ++j) read_b(fb0, lds, b_off0, j);
+    for (int j = 0; j < TJ; ++j) read_b(fbe, lds, j);
 #pragma unroll
-    for (int m = 0; m < TM; ++m) read_a(fa0, lds, a_off0, m);
+    for (int i = 0; i < TI - 2; ++i) read_a(lds, i);
     int slot = 0;
-    // `first` = std::true_type: first K32 chunk of a vocabulary tile (its first K16 step starts the accumulators from 0)
+    // One K32 chunk: 32 MFMAs, vocabulary block by vocabulary block.  W fragment i of the next slot (its W part
+    // was certified one barrier earlier) is read into fa[i] once row i of MFMAs has been issued - the last two
+    // only at the start of the next iteration, long before their rows.  The workgroup barrier sits in the middle
+    // of the iteration; the H fragments of the next slot are read right after it into the other fragment set, with
+    // four rows of MFMAs (256 cycles of this wave alone) to cover the 8 waves' reads queueing on the LDS.  Even
+    // iterations (stream = H lines) compute on fbe, odd ones on fbo.
+    // `first`: first chunk of a vocabulary tile - the addend is the constant 0, so the accumulators are never cleared.
     auto iteration = [&](auto stream, auto first) {
+        constexpr bool is_b = decltype(stream)::value;
         constexpr bool is_first = decltype(first)::value;
         const unsigned char* cur = lds + slot * C::SLOT_BYTES;
         slot = slot + 1 == RING ? 0 : slot + 1;
         const unsigned char* nxt = lds + slot * C::SLOT_BYTES;
-        auto m0 = [&](int x) { if constexpr (is_first) mma0(fa0, fb0, x); else mma(fa0, fb0, x); };
-        // ---- K16 step 0 -------------------------------------------------------------------------
-        m0(0); m0(1);
+        bf16x8 (&fb)[TJ] = is_b ? fbe : fbo;
+        bf16x8 (&fbn)[TJ] = is_b ? fbo : fbe;
+        // consecutive MFMAs always share an operand: token blocks ascend on even rows and descend on odd ones
+        // (in a register-only loop under the power limit this order sustained 4 % more than plain row-major)
+        auto row = [&](int i) {
+#pragma unroll
+            for (int jj = 0; jj < TJ; ++jj) {
+                const int j = (i & 1) ? TJ - 1 - jj : jj;
+                if constexpr (is_first) {
+                    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fb[j], zero, 0, 0, 0);
+                } else {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                }
+            }
+        };
+        read_a(cur, 6); read_a(cur, 7);
         __builtin_amdgcn_sched_barrier(0);
-        read_b(fb1, cur, b_off1, 0); read_b(fb1, cur, b_off1, 1);
+        row(0);
+        __builtin_amdgcn_sched_barrier(0);
+        read_a(nxt, 0);
         issue_one(stream, 0);
         __builtin_amdgcn_sched_barrier(0);
-        m0(2); m0(3);
+        row(1);
         __builtin_amdgcn_sched_barrier(0);
-        read_a(fa1, cur, a_off1, 0); read_a(fa1, cur, a_off1, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        m0(4); m0(5);
-        __builtin_amdgcn_sched_barrier(0);
-        read_a(fa1, cur, a_off1, 2); read_a(fa1, cur, a_off1, 3);
+        read_a(nxt, 1);
         issue_one(stream, 1);
         __builtin_amdgcn_sched_barrier(0);
-        m0(6); m0(7);
+        row(2);
         __builtin_amdgcn_sched_barrier(0);
-        // ---- K16 step 1 -------------------------------------------------------------------------
-        mma(fa1, fb1, 0); mma(fa1, fb1, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        read_a(fa0, nxt, a_off0, 0); read_a(fa0, nxt, a_off0, 1);           // W part of slot i+1: certified already
         issue_one(stream, 2);
         __builtin_amdgcn_sched_barrier(0);
-        mma(fa1, fb1, 2); mma(fa1, fb1, 3);
-        __builtin_amdgcn_sched_barrier(0);
-        // everything this wave requested before this iteration has landed (3 younger loads may fly);
-        // its own LDS reads are complete; then all waves agree
-        wait_vmcnt<3>();
-        __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0) only
-        __syncthreads();
-        read_b(fb0, nxt, b_off0, 0); read_b(fb0, nxt, b_off0, 1);           // H part of slot i+1: certified just now
-        read_a(fa0, nxt, a_off0, 2); read_a(fa0, nxt, a_off0, 3);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(fa1, fb1, 4); mma(fa1, fb1, 5);
+        row(3);
         __builtin_amdgcn_sched_barrier(0);
         issue_one(stream, 3); advance(stream);
+        // everything this wave requested before this iteration has landed (its own 4 loads may fly); its own
+        // LDS reads are complete (the last one was issued two rows of MFMAs ago); then all waves agree
+        wait_vmcnt<4>();
+        __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0) only
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < TJ; ++j) read_b(fbn, nxt, j);                    // H part of slot i+1: certified just now
         __builtin_amdgcn_sched_barrier(0);
-        mma(fa1, fb1, 6); mma(fa1, fb1, 7);
+        row(4);
+        __builtin_amdgcn_sched_barrier(0);
+        read_a(nxt, 2); read_a(nxt, 3);                                      // behind every wave's H reads in the LDS queue
+        __builtin_amdgcn_sched_barrier(0);
+        row(5);
+        __builtin_amdgcn_sched_barrier(0);
+        read_a(nxt, 4); read_a(nxt, 5);
+        __builtin_amdgcn_sched_barrier(0);
+        row(6);
+        __builtin_amdgcn_sched_barrier(0);
+        row(7);
     };
-    // even iteration i requests the H lines of pair i/2 + 1, odd iteration i+1 the W lines of pair i/2 + 2; past the
-    // last pair both streams keep requesting lines that exist, into slots nobody reads, so there is no drain variant
+    static_assert(TI == 8 && TJ == 4, "the hand-placed schedule above");
     for (int vt = vt_lo; vt < vt_hi; ++vt) {
         iteration(kB, std::true_type{});
         iteration(kA, std::false_type{});
@@ -542,13 +667,25 @@ __global__ __launch_bounds__(C::NT) void logprob_ring_kernel(LogprobArgs a) {
             iteration(kB, std::false_type{});
             iteration(kA, std::false_type{});
         }
-        tile_epilogue<TM, TN, BM / C::WM, false>(acc, st, vt * BM + wm * (BM / C::WM), a.V, lh);
+        tile_epilogue16<TI, TJ, BM / C::WM>(acc, st, vt * BM + wm * (BM / C::WM), a.V, lq, tgt_wave, tgt_valid, l15);
+        // The fragments of the next chunk are read again here rather than kept across the epilogue: held, their
+        // 64 registers pushed the epilogue into scratch memory, whose latency nothing hides (every wave of the
+        // workgroup is in its epilogue at the same time).  The slot is certified and not yet released.
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+        {
+            const unsigned char* nxt = lds + slot * C::SLOT_BYTES;
+#pragma unroll
+            for (int j = 0; j < TJ; ++j) read_b(fbe, nxt, j);
+#pragma unroll
+            for (int i = 0; i < TI - 2; ++i) read_a(nxt, i);   // the last two: at the start of the iteration
+        }
     }
     wait_vmcnt<0>();
     __builtin_amdgcn_s_waitcnt(0xC07F);
     __syncthreads();   // every fragment read and every load into LDS has finished
-    write_partials<TN, C::WM, C::WN, BN, C::NT>(st, reinterpret_cast<float*>(lds), wm, wn, l31, lh, tid, tok0,
-                                                 a.T, sp, a.part);
+    write_partials16<TJ, C::WM, C::WN, BN, C::NT>(st, reinterpret_cast<float*>(lds), wm, wn, l15, lq, tid, tok0,
+                                                   a.T, sp, a.part);
 }
 
 __global__ __launch_bounds__(256) void logprob_finalize_kernel(

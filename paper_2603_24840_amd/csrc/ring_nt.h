@@ -223,7 +223,6 @@ __device__ __forceinline__ void walk(const Walk& w, unsigned char* lds, f32x16 (
     auto read_b = [&](bf16x8 (&fb)[TN], const unsigned char* base, int k16, int j) {   // k16: K16 step 0 / 1 of the slot
         if constexpr (B_KMAJOR) {
             typedef short s16x4 __attribute__((ext_vector_type(4)));
-            typedef short s16x8 __attribute__((ext_vector_type(8)));
             typedef __attribute__((address_space(3))) s16x4* lds_s16x4_t;
             const int step = k16 * 16 * 512;
             const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t)(base + ((bt_off[0] ^ (j << 6)) + step)));
