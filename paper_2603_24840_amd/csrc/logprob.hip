@@ -401,15 +401,15 @@ __global__ __launch_bounds__(C::NT) void logprob_kernel(LogprobArgs a) {
 // Loads always fetch whole 128-byte lines of a row, i.e. the two K32 halves that go to two
 // consecutive slots (a "pair").  The L1 path moves 64 bytes per clock, so a pair costs as many L1
 // cycles as half of its MFMA time; to keep that evenly spread, the W lines ("A") of a pair are
-// requested during one K32 iteration and its H lines ("B") during the next, all four load instructions of an
-// iteration in its first half.  The pipeline per iteration i (chunk i lives in slot i % RING, its fragments
-// are in registers when the iteration starts):
-//   rows 0-3 of MFMAs (a row = one vocabulary block x the 4 token blocks); W fragment r of slot i+1 is read
+// requested during one K32 iteration and its H lines ("B") during the next, two load instructions before the
+// iteration's barrier and two right behind it.  The pipeline per iteration i (chunk i lives in slot i % RING, its
+// fragments are in registers when the iteration starts):
+//   rows 0-2 of MFMAs (a row = one vocabulary block x the 4 token blocks); W fragment r of slot i+1 is read
 //               into the registers of W fragment r as soon as row r has been issued (the W part of slot i+1
 //               was certified one barrier earlier);
 //   the wait for this wave's older loads, the workgroup barrier;
-//   the H fragments of slot i+1 (certified just now) into the second H fragment set, then rows 4-7 with the
-//               remaining W fragment reads between them: four rows of MFMAs cover the eight waves' reads
+//   the H fragments of slot i+1 (certified just now) into the second H fragment set, then rows 3-7 with the
+//               remaining W fragment reads between them: five rows of MFMAs cover the eight waves' reads
 //               queueing on the LDS, so the matrix pipe never waits for an LDS round trip behind a barrier.
 // The barrier inside iteration i certifies the W part of slot i+2 and the H part of slot i+1; every read of
 // slot i has completed by then (they were issued during iteration i-1 and at the start of iteration i), so
@@ -593,10 +593,13 @@ __global__ __launch_bounds__(C::NT) void logprob_ring_kernel(LogprobArgs a) {
     int slot = 0;
     // One K32 chunk: 32 MFMAs, vocabulary block by vocabulary block.  W fragment i of the next slot (its W part
     // was certified one barrier earlier) is read into fa[i] once row i of MFMAs has been issued - the last two
-    // only at the start of the next iteration, long before their rows.  The workgroup barrier sits in the middle
-    // of the iteration; the H fragments of the next slot are read right after it into the other fragment set, with
-    // four rows of MFMAs (256 cycles of this wave alone) to cover the 8 waves' reads queueing on the LDS.  Even
-    // iterations (stream = H lines) compute on fbe, odd ones on fbo.
+    // only at the start of the next iteration, long before their rows.  The workgroup barrier sits after the third
+    // row; the H fragments of the next slot are read right after it into the other fragment set, with five rows of
+    // MFMAs to cover the 8 waves' reads queueing on the LDS.  Two of the four loads go out before the barrier and
+    // two right behind it: of the placements tried at the benchmark sizes (all four before it, barrier after row
+    // 1 ... 5, loads spread over the rows) this one was the fastest on the workloads' data (+4-6 % over all four
+    // before a barrier after row 3) and fetched the fewest bytes from beyond the L2; on all-zero operands it is 8 %
+    // slower than that one.  Even iterations (stream = H lines) compute on fbe, odd ones on fbo.
     // `first`: first chunk of a vocabulary tile - the addend is the constant 0, so the accumulators are never cleared.
     auto iteration = [&](auto stream, auto first) {
         constexpr bool is_b = decltype(stream)::value;
@@ -626,30 +629,32 @@ __global__ __launch_bounds__(C::NT) void logprob_ring_kernel(LogprobArgs a) {
         __builtin_amdgcn_sched_barrier(0);
         read_a(nxt, 0);
         issue_one(stream, 0);
+        issue_one(stream, 1);
         __builtin_amdgcn_sched_barrier(0);
         row(1);
         __builtin_amdgcn_sched_barrier(0);
         read_a(nxt, 1);
-        issue_one(stream, 1);
         __builtin_amdgcn_sched_barrier(0);
         row(2);
         __builtin_amdgcn_sched_barrier(0);
-        issue_one(stream, 2);
-        __builtin_amdgcn_sched_barrier(0);
-        row(3);
-        __builtin_amdgcn_sched_barrier(0);
-        issue_one(stream, 3); advance(stream);
-        // everything this wave requested before this iteration has landed (its own 4 loads may fly); its own
-        // LDS reads are complete (the last one was issued two rows of MFMAs ago); then all waves agree
-        wait_vmcnt<4>();
+        // everything this wave requested before this iteration has landed (vmcnt counts in order: its two loads of
+        // this iteration may fly, the two it issued behind the previous barrier may not); its own LDS reads are
+        // complete (the last one was issued a row of MFMAs ago); then all waves agree
+        wait_vmcnt<2>();
         __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0) only
         __syncthreads();
 #pragma unroll
         for (int j = 0; j < TJ; ++j) read_b(fbn, nxt, j);                    // H part of slot i+1: certified just now
         __builtin_amdgcn_sched_barrier(0);
+        row(3);
+        __builtin_amdgcn_sched_barrier(0);
+        read_a(nxt, 2);                                                      // behind every wave's H reads in the LDS queue
+        issue_one(stream, 2);
+        issue_one(stream, 3); advance(stream);
+        __builtin_amdgcn_sched_barrier(0);
         row(4);
         __builtin_amdgcn_sched_barrier(0);
-        read_a(nxt, 2); read_a(nxt, 3);                                      // behind every wave's H reads in the LDS queue
+        read_a(nxt, 3);
         __builtin_amdgcn_sched_barrier(0);
         row(5);
         __builtin_amdgcn_sched_barrier(0);
@@ -657,7 +662,11 @@ __global__ __launch_bounds__(C::NT) void logprob_ring_kernel(LogprobArgs a) {
         __builtin_amdgcn_sched_barrier(0);
         row(6);
         __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_sched_barrier(0);
         row(7);
+        __builtin_amdgcn_sched_barrier(0);
+        // (the scheduling fence after the last row matters: without it the compiler lets the next iteration's first
+        // reads drift up into this one and the kernel loses 10 %)
     };
     static_assert(TI == 8 && TJ == 4, "the hand-placed schedule above");
     for (int vt = vt_lo; vt < vt_hi; ++vt) {
