@@ -35,10 +35,10 @@ ALL_WORKLOADS = ["tiny", "llama1b", "qwen1p7b", "llama3b", "qwen8b"]
 # (hbm_traffic_<workload>.txt).  For the log-prob kernel the figure is the fetch at the L2 <-> fabric
 # interface, Infinity-Cache hits included.  None where not measured.
 PROFILED_TRAFFIC_BYTES = {
-    ("llama1b", "logprob"): 3.0339e+11, ("llama1b", "compact"): 8.5946e+09,
-    ("qwen1p7b", "logprob"): 1.4523e+12, ("qwen1p7b", "compact"): 1.2027e+11,
-    ("llama3b", "logprob"): 1.8889e+12, ("llama3b", "compact"): 1.2027e+11,
-    ("qwen8b", "logprob"): 5.5199e+12, ("qwen8b", "compact"): 1.5464e+11,
+    ("llama1b", "logprob"): 3.3619e+11, ("llama1b", "compact"): 8.5949e+09,
+    ("qwen1p7b", "logprob"): 1.0884e+12, ("qwen1p7b", "compact"): 1.2027e+11,
+    ("llama3b", "logprob"): 1.7869e+12, ("llama3b", "compact"): 1.2027e+11,
+    ("qwen8b", "logprob"): 4.4537e+12, ("qwen8b", "compact"): 1.5464e+11,
 }
 
 
