@@ -209,7 +209,12 @@ def test_logprob_full_size_sampled_rows(A, W, name):
     # whole output: finite, negative, and distributed as logits ~ N(0,1) imply (lse ~ log V + 1/2)
     assert bool(torch.isfinite(lp).all()) and float(lp.max()) <= 0.0
     assert abs(float(lse.mean()) - (np.log(cfg.vocab) + 0.5)) < 0.05
-    del hidden, lm_head, lp, lse
+    # every sum is taken in a fixed order: a second pass gives the same bits on all T rows (a workgroup that read an
+    # LDS slot before its loads had landed, or after it was refilled, would show up here)
+    lp2, lse2 = A.arrol_logprob(hidden, lm_head, targets, want_lse=True)
+    torch.cuda.synchronize()
+    assert torch.equal(lp, lp2) and torch.equal(lse, lse2)
+    del hidden, lm_head, lp, lse, lp2, lse2
     free()
 
 
