@@ -21,7 +21,7 @@
 namespace {
 
 using ring_nt::bf16x8;
-using ring_nt::f32x16;
+typedef float f32x16 __attribute__((ext_vector_type(16)));   // 32x32x16 accumulators of the tile and small-batch kernels
 
 constexpr int kThreads = 256;
 constexpr int BU = 256;   // hidden units per pass
@@ -423,12 +423,12 @@ __global__ __launch_bounds__(256) void score_mlp_small_finish_kernel(const float
 
 // ---------------------------------------------------------------------------------------------------------
 // Large batches (more than kSmallMaxRows rollouts, d a multiple of 64, rows addressed without row_index):
-// the same three contractions on the 8-wavefront direct-to-LDS ring pipeline of ring_nt.h, one 256 x 256
-// accumulator tile per workgroup: grid = (blocks of 256 B rows, tiles of 256 A rows, K splits).
+// the contractions on the 8-wavefront direct-to-LDS ring pipeline of ring_nt.h (v_mfma_f32_16x16x32_bf16), one
+// 256 x 256 accumulator tile per workgroup: grid = (blocks of 256 B rows, tiles of 256 A rows, K splits).
 //   forward  A = W1 [m, d], B = hidden [N, d]: bias + ReLU + w2 dot per rollout (lane-local over the
 //            units), partial scores [unit tile][rollout] to the workspace, summed by the finish kernel;
 //            for the gradient call the same pass also keeps the activations a = relu(pre) in fp32, unit-major
-//            (the accumulator's own layout: 32 lanes = 32 consecutive rollouts), so that nothing is recomputed:
+//            (the accumulator's own layout: 16 lanes = 16 consecutive rollouts), so that nothing is recomputed:
 //            delta^T = r w2 [a > 0] and the per-unit sums are then one streaming pass (mlp_delta_kernel);
 //   wgrad    A = delta^T [m, n_pad], B = the hidden states themselves, [N, d] = K-major (ring_nt's TN form, no
 //            transposed copy), over K = rollouts (split): fp32 tile stores.
@@ -448,12 +448,12 @@ template <int MODE>
 __global__ __launch_bounds__(RingCfg::NT) void mlp_ring_kernel(MlpRingArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     using C = RingCfg;
-    constexpr int BM = C::BM, BN = C::BN, TM = C::TM, TN = C::TN;
+    constexpr int BM = C::BM, BN = C::BN, TI = C::TI, TJ = C::TJ;
     const int tb = blockIdx.x, vt = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / C::WN, wn = wave % C::WN;
-    const int l31 = lane & 31, lh = lane >> 5;
+    const int l15 = lane & 15, lq = lane >> 4;
     const int k64_lo = MODE == kWgrad ? static_cast<int>(blockIdx.z) * a.k64_per_split : 0;
     const int k64_hi = MODE == kWgrad ? (k64_lo + a.k64_per_split < a.n_k64 ? k64_lo + a.k64_per_split : a.n_k64) : a.n_k64;
 
@@ -466,56 +466,56 @@ __global__ __launch_bounds__(RingCfg::NT) void mlp_ring_kernel(MlpRingArgs a) {
     w.b_stride = a.b_stride;
     w.a_rows = a.a_rows - vt * BM;
     w.b_rows = a.b_rows - tb * BN < BN ? a.b_rows - tb * BN : BN;
-    w.n_tiles = 1;
     w.n_k64 = k64_hi > k64_lo ? k64_hi - k64_lo : 0;
     w.b_k_rows = a.b_k_rows - k64_lo * 64;
 
     const int unit0 = vt * BM + wm * (BM / C::WM);           // first A row of this wavefront
     const int row0 = tb * BN + wn * (BN / C::WN);            // first B row of this wavefront
-    float part[TN] = {0.f, 0.f};
-    f32x16 acc[TM][TN];
-    ring_nt::walk<C, MODE == kWgrad>(w, lds, acc, [](f32x16 (&)[TM][TN], int) {});   // one tile: the epilogue runs here, after the walk
+    float part[TJ] = {0.f, 0.f, 0.f, 0.f};
+    ring_nt::f32x4 acc[TI][TJ];
+    ring_nt::walk<C, MODE == kWgrad>(w, lds, acc);
     {
-        // acc[i][j][v]: A row unit0 + i*32 + (v/4)*8 + lh*4 + v%4, B row row0 + j*32 + l31
+        // acc[i][j][v]: A row unit0 + i*16 + lq*4 + v, B row row0 + j*16 + l15
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TI; ++i)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int u = unit0 + i * 32 + (v >> 2) * 8 + lh * 4 + (v & 3);
+            for (int v = 0; v < 4; ++v) {
+                const int u = unit0 + i * 16 + lq * 4 + v;
                 const bool live = u < a.a_rows;
                 if (MODE == kWgrad) {
                     float* crow = a.c_out + (static_cast<int64_t>(blockIdx.z) * a.a_rows + u) * a.c_stride;
 #pragma unroll
-                    for (int j = 0; j < TN; ++j) {
-                        const int col = row0 + j * 32 + l31;
+                    for (int j = 0; j < TJ; ++j) {
+                        const int col = row0 + j * 16 + l15;
                         if (live && col < a.b_rows) crow[col] = acc[i][j][v];
-                        acc[i][j][v] = 0.f;
                     }
                 } else {
                     const float bias = (live && a.b1) ? a.b1[u] : 0.f;
                     const float wu = live ? a.w2[u] : 0.f;
                     float* arow = MODE == kForwardKeep ? a.act_t + static_cast<int64_t>(live ? u : 0) * a.act_stride : nullptr;
 #pragma unroll
-                    for (int j = 0; j < TN; ++j) {
+                    for (int j = 0; j < TJ; ++j) {
                         const float act = fmaxf(acc[i][j][v] + bias, 0.f);
                         part[j] = fmaf(act, wu, part[j]);
                         if (MODE == kForwardKeep) {
-                            const int col = row0 + j * 32 + l31;
+                            const int col = row0 + j * 16 + l15;
                             if (live && col < a.b_rows) arow[col] = act;
                         }
-                        acc[i][j][v] = 0.f;
                     }
                 }
             }
     }
     if (MODE == kWgrad) return;
-    // the two lane halves and the two wavefront rows hold different units of the same rollouts
+    // the four lane quarters and the two wavefront rows hold different units of the same rollouts
     float* red = reinterpret_cast<float*>(lds);   // [WM][BN]
 #pragma unroll
-    for (int j = 0; j < TN; ++j) part[j] += __shfl_xor(part[j], 32, ARROL_WAVE);
-    if (lh == 0) {
+    for (int j = 0; j < TJ; ++j) {
+        part[j] += __shfl_xor(part[j], 16, ARROL_WAVE);
+        part[j] += __shfl_xor(part[j], 32, ARROL_WAVE);
+    }
+    if (lq == 0) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) red[wm * BN + wn * (BN / C::WN) + j * 32 + l31] = part[j];
+        for (int j = 0; j < TJ; ++j) red[wm * BN + wn * (BN / C::WN) + j * 16 + l15] = part[j];
     }
     __syncthreads();
     for (int col = tid; col < BN; col += C::NT) {
