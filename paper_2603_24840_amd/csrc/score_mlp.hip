@@ -572,6 +572,47 @@ __global__ __launch_bounds__(1024) void mlp_residual_kernel(const float* __restr
     }
 }
 
+// The gradient call after a forward pass that leaves partial scores (partial[unit block][rollout]):
+// score_mlp_small_finish_kernel and mlp_residual_kernel in one launch - score = sum over the unit blocks in index
+// order + b2, then r_i and the loss terms as above; neither scores nor probabilities go to memory.
+__global__ __launch_bounds__(1024) void mlp_finish_residual_kernel(const float* __restrict__ partial, int n_ub,
+                                                                   float b2, const float* __restrict__ labels,
+                                                                   int n_rows, float* __restrict__ resid,
+                                                                   float* __restrict__ block_sums) {
+    __shared__ float red[2][16];
+    const float inv_n = 1.f / static_cast<float>(n_rows);
+    float loss = 0.f, rs = 0.f;
+    const int i = blockIdx.x * 1024 + threadIdx.x;
+    if (i < n_rows) {
+        float s = 0.f;
+        for (int ub = 0; ub < n_ub; ++ub) s += partial[static_cast<int64_t>(ub) * n_rows + i];
+        s += b2;
+        float q;
+        if (s >= 0.f) {
+            q = 1.f / (1.f + expf(-s));
+        } else {
+            const float e = expf(s);
+            q = e / (1.f + e);
+        }
+        const float y = labels[i];
+        const float r = (q - y) * inv_n;
+        resid[i] = r;
+        rs = r;
+        loss = fmaxf(s, 0.f) - y * s + log1pf(expf(-fabsf(s)));
+    }
+    loss = wave_sum_f32(loss);
+    rs = wave_sum_f32(rs);
+    const int lane = threadIdx.x & (ARROL_WAVE - 1), wave = threadIdx.x / ARROL_WAVE;
+    if (lane == 0) { red[0][wave] = loss; red[1][wave] = rs; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float a = 0.f, b = 0.f;
+        for (int w = 0; w < 16; ++w) { a += red[0][w]; b += red[1][w]; }
+        block_sums[blockIdx.x] = a;
+        block_sums[gridDim.x + blockIdx.x] = b;
+    }
+}
+
 __global__ void mlp_residual_finish_kernel(const float* __restrict__ block_sums, int n_blocks, int n_rows,
                                            float* __restrict__ loss_out, float* __restrict__ grad_b2) {
     float a = 0.f, b = 0.f;
@@ -584,6 +625,7 @@ __global__ void mlp_residual_finish_kernel(const float* __restrict__ block_sums,
 //   delta^T[u][i] = r_i w2_u [a_ui > 0] (bf16, 0 for n_rows <= i < n_pad; optionally the bf16 remainder too),
 //   dL/dw2_u = sum_i r_i a_ui,  dL/db1_u = sum_i r_i w2_u [a_ui > 0],
 // each lane over its own columns in ascending order, then lanes, then wavefronts: a fixed summation order.
+// Workgroup 0 also finishes the loss and dL/db2 from the residual pass's block sums.
 constexpr int kDeltaThreads = 1024;
 __global__ __launch_bounds__(kDeltaThreads) void mlp_delta_kernel(const float* __restrict__ act_t, int64_t act_stride,
                                                                   const float* __restrict__ resid,
@@ -591,9 +633,18 @@ __global__ __launch_bounds__(kDeltaThreads) void mlp_delta_kernel(const float* _
                                                                   uint16_t* __restrict__ delta_t,
                                                                   uint16_t* __restrict__ delta_lo,
                                                                   float* __restrict__ grad_w2,
-                                                                  float* __restrict__ grad_b1) {
+                                                                  float* __restrict__ grad_b1,
+                                                                  const float* __restrict__ block_sums, int n_blocks,
+                                                                  float* __restrict__ loss_out,
+                                                                  float* __restrict__ grad_b2) {
     __shared__ float red[2][kDeltaThreads / ARROL_WAVE];
     const int u = blockIdx.x;
+    if (u == 0 && threadIdx.x == 0) {   // loss and dL/db2: the residual pass's block sums, added in block order
+        float a = 0.f, b = 0.f;
+        for (int k = 0; k < n_blocks; ++k) { a += block_sums[k]; b += block_sums[n_blocks + k]; }
+        if (loss_out) *loss_out = a / static_cast<float>(n_rows);
+        if (grad_b2) *grad_b2 = b;
+    }
     const float wu = w2[u];
     const float* arow = act_t + static_cast<int64_t>(u) * act_stride;
     uint16_t* drow = delta_t + static_cast<int64_t>(u) * n_pad;
@@ -851,7 +902,7 @@ extern "C" int arrol_score_mlp_grad(const void* hidden, int64_t row_stride_elems
     float* act = reinterpret_cast<float*>(ws + p.off_act);
     float* partial = reinterpret_cast<float*>(ws + p.off_small);
     bool kept = true;
-    int rc = ARROL_OK;
+    int rc = ARROL_OK, n_ub = 0;
     if (ring_applies(n_rows, d, row_stride_elems, row_index)) {
         MlpRingArgs r = {};
         r.a = a.w1; r.a_stride = static_cast<unsigned>(d) * 2; r.a_rows = m;
@@ -860,29 +911,28 @@ extern "C" int arrol_score_mlp_grad(const void* hidden, int64_t row_stride_elems
         r.act_t = act; r.act_stride = p.n_pad;
         rc = launch_mlp_ring<kForwardKeep>(r, dim3((n_rows + 255) / 256, p.r_vt), st);
         if (rc != ARROL_OK) return rc;
-        arrol_launch(score_mlp_small_finish_kernel, dim3((n_rows + 255) / 256), dim3(256), 0, st, partial, p.r_vt,
-                     n_rows, b2, score, prob);
+        n_ub = p.r_vt;
     } else if (d % 64 == 0 && n_rows <= kSmallMaxRows) {
-        const int n_ub = (m + 31) / 32;
+        n_ub = (m + 31) / 32;
         arrol_launch(score_mlp_small_kernel, dim3((n_rows + 31) / 32, n_ub), dim3(kSmallThreads), 0, st,
                      a.hidden, row_stride_elems, row_index, a.w1, b1, w2, n_rows, d, m, n_ub, partial, act,
                      static_cast<int64_t>(p.n_pad));
-        arrol_launch(score_mlp_small_finish_kernel, dim3((n_rows + 255) / 256), dim3(256), 0, st, partial, n_ub,
-                     n_rows, b2, score, prob);
     } else {
         kept = false;
         rc = launch_mlp<kForward>(a, dim3(p.n_rb), st);
         if (rc != ARROL_OK) return rc;
     }
     if (arrol_launch_failed()) return arrol_launch_status();
-    // residuals and loss
-    arrol_launch(mlp_residual_kernel, dim3(n_rblocks), dim3(1024), 0, st, score, prob, labels, n_rows, resid, bsum);
-    arrol_launch(mlp_residual_finish_kernel, dim3(1), dim3(1), 0, st, bsum, n_rblocks, n_rows, loss_out, grad_b2);
-    // delta^T and the per-unit sums
     if (kept) {
+        // scores from the partials, residuals and loss terms in one launch; delta^T, the per-unit sums, the loss
+        // and dL/db2 in the next
+        arrol_launch(mlp_finish_residual_kernel, dim3(n_rblocks), dim3(1024), 0, st, partial, n_ub, b2, labels, n_rows,
+                     resid, bsum);
         arrol_launch(mlp_delta_kernel, dim3(m), dim3(kDeltaThreads), 0, st, act, static_cast<int64_t>(p.n_pad), resid, w2,
-                     n_rows, p.n_pad, dt, dt_lo, grad_w2, grad_b1);
+                     n_rows, p.n_pad, dt, dt_lo, grad_w2, grad_b1, bsum, n_rblocks, loss_out, grad_b2);
     } else {
+        arrol_launch(mlp_residual_kernel, dim3(n_rblocks), dim3(1024), 0, st, score, prob, labels, n_rows, resid, bsum);
+        arrol_launch(mlp_residual_finish_kernel, dim3(1), dim3(1), 0, st, bsum, n_rblocks, n_rows, loss_out, grad_b2);
         a.resid = resid; a.delta_t = dt; a.delta_lo = dt_lo; a.delta_stride = p.n_pad; a.unit_partial = unit;
         rc = launch_mlp<kDelta>(a, dim3(p.n_rb), st);
         if (rc != ARROL_OK) return rc;
