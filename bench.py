@@ -14,6 +14,7 @@ reported, with their own rooflines and oracle parity on a sample, under "all_con
   python bench.py --calibrate-copy      # plain 1 GiB device copy, for scaling rocprof byte counters
   python bench.py --extras              # adds timings of the calls outside the five-stage step
   python bench.py --only logprob --input-data zeros   # profiling aids (see profiles/)
+  python bench.py --only logprob --mfma-probe         # register-only MFMA rate of this card beside the kernel's
 """
 import argparse
 import json
@@ -66,6 +67,9 @@ def parse():
     ap.add_argument("--input-data", default="randn", choices=["randn", "zeros"],
                     help="contents of the log-prob operands: the workload's N(0,1) recipe, or all zeros "
                          "(same kernel and launch, no operand toggling: shows the clock the part reaches without a power limit)")
+    ap.add_argument("--mfma-probe", action="store_true",
+                    help="also with --only / --input-data: time the register-only MFMA loops (on by default otherwise)")
+    ap.add_argument("--skip-mfma-probe", action="store_true")
     ap.add_argument("--vendor-gemm", action="store_true",
                     help="also time the ROCm BLAS bf16 GEMM (torch.matmul) on the first 32,768 rows of the same log-prob "
                          "operands: the matrix throughput a vendor-tuned kernel sustains on this data, for context")
@@ -351,6 +355,30 @@ def time_vendor_gemm(wl, torch, rows=32768, reps=10):
                     % (n, wl.cfg.d, wl.cfg.vocab, wl.cfg.d), "ms": ms, "TFLOPs": tf, "frac_of_peak": tf / MFMA_BF16_PEAK_TFLOPS}
 
 
+def time_mfma_probe(A, wl, torch, iters=300000):
+    """Register-only bf16 MFMA loops (arrol_probe_mfma_rate: no LDS, no memory traffic, 2 wavefronts per SIMD on all
+    256 CUs) on the first values of the log-prob operands and on zeros: what this card's matrix cores sustain under
+    its power limit.  Not part of the path; it puts the log-prob kernel's rate beside the card's own ceiling."""
+    n = min(64 * 8 * 12 * 256, wl.lp_hidden.numel() // 512 * 512, wl.lm_head.numel() // 512 * 512)
+    a_r, b_r = wl.lp_hidden.reshape(-1)[:n].contiguous(), wl.lm_head.reshape(-1)[:n].contiguous()
+    zeros = torch.zeros(n, dtype=torch.bfloat16, device=wl.dev)
+    sink = torch.empty(256 * 512, dtype=torch.float32, device=wl.dev)
+    out = {"what": "v_mfma bf16 from registers only, 256 workgroups x 8 wavefronts, %d iterations of 32 (16) "
+                   "instructions per wavefront; TFLOP/s by HIP events" % iters}
+    for data, (a, b) in (("randn", (a_r, b_r)), ("zeros", (zeros, zeros))):
+        out[data] = {}
+        for shape, name in ((16, "16x16x32"), (32, "32x32x16")):
+            A.arrol_probe_mfma_rate(a, b, shape=shape, iters=iters // 3, out_sink=sink)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            _, flop = A.arrol_probe_mfma_rate(a, b, shape=shape, iters=iters, out_sink=sink)
+            e1.record()
+            torch.cuda.synchronize()
+            out[data][name] = round(flop / e0.elapsed_time(e1) / 1e9, 1)
+    out["frac_of_peak_randn_16x16x32"] = out["randn"]["16x16x32"] / MFMA_BF16_PEAK_TFLOPS
+    return out
+
+
 def time_extras(A, W, cfg, dev, torch, lp_hidden, lm_head, targets, cu, reps=10):
     """HIP-event timings of the calls that are not part of the five-stage step, at this workload's shapes.
     Each figure is the mean over `reps` back-to-back calls after two warm-up calls."""
@@ -545,6 +573,8 @@ def main():
     torch.cuda.empty_cache()
     if args.vendor_gemm:
         result["vendor_gemm_reference"] = time_vendor_gemm(wl, torch)
+    if args.mfma_probe or not (profiling or args.skip_mfma_probe):
+        result["mfma_register_loop"] = time_mfma_probe(A, wl, torch)
     if args.extras:
         result["extras"] = time_extras(A, W, cfg, dev, torch, wl.lp_hidden, wl.lm_head, wl.targets, wl.cu)
     del wl

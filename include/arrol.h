@@ -14,6 +14,7 @@
  *   arrol_score_grad, arrol_score_mlp_grad, arrol_adamw_step  training the head on the fly (Sec. 4.2, 4.3 (iii); Alg. 1)
  *   arrol_compact_inplace                                      hole-filling compaction of the same pool (Sec. 4.3 (i))
  *   arrol_compact_static                                       arrol_compact without a workspace argument (fixed scratch)
+ *   arrol_probe_mfma_rate                                      measurement aid: register-only bf16 MFMA rate of this card
  *   arrol_token_confidence, arrol_trace_confidence             trace confidence (Sec. 3)
  *   arrol_grpo_advantage, arrol_grpo_objective                 group-relative advantage, clipped objective (Sec. 3)
  *
@@ -391,6 +392,22 @@ int arrol_score_mlp_grad(const void* hidden, int64_t row_stride_elems, const int
 int arrol_adamw_step(float* param, const float* grad, float* m, float* v, int64_t n, int32_t step,
                      float lr, float beta1, float beta2, float eps, float weight_decay,
                      void* param_bf16, void* stream);
+
+/*
+ * Measurement aid for the benchmark, not a stage of the path (the paper defines no such call): runs bf16
+ * MFMAs from registers alone - no LDS, no memory traffic in the loop, 8 wavefronts per workgroup, the
+ * accumulator shape of the log-prob kernel - and so shows what this card's matrix cores sustain on the given
+ * operand VALUES: the part lowers its clock under a power limit when operands toggle, not when they are zero.
+ * a_bf16 [n_a], b_bf16 [n_b]: device, bf16, 16-byte aligned, n_a and n_b positive multiples of 512 (whole
+ * 64-lane fragments); each wavefront takes 8 A and 4 B fragments round-robin from them, once, before the loop.
+ * shape: 16 -> v_mfma_f32_16x16x32_bf16 (32 instructions per iteration), 32 -> v_mfma_f32_32x32x16_bf16 (16).
+ * n_workgroups in [1, 65536] workgroups of 512 lanes; iters >= 0 loop iterations of 524,288 flop per wavefront.
+ * sink: device fp32 [n_workgroups * 512], receives each lane's sum of its accumulators (iters * the lane's share
+ * of A B^T, fp32 accumulation order fixed).  flop_out: host double or NULL, receives the launch's flop count.
+ * Asynchronous on `stream`; time it with events.  Anything else -> ARROL_EINVAL, nothing enqueued.
+ */
+int arrol_probe_mfma_rate(const void* a_bf16, int64_t n_a, const void* b_bf16, int64_t n_b, int32_t shape,
+                          int32_t n_workgroups, int32_t iters, float* sink, double* flop_out, void* stream);
 
 #ifdef __cplusplus
 }

@@ -75,6 +75,7 @@ _SIGNATURES = {
     "arrol_histogram": (ctypes.c_int, [_vp, _vp, _i64, _i32, _vp, _vp, _vp]),
     "arrol_calibrate": (ctypes.c_int, [_vp, _vp, _i32, Policy, _vp, _vp, _vp, _vp]),
     "arrol_prune_bernoulli": (ctypes.c_int, [_vp, _vp, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _vp]),
+    "arrol_probe_mfma_rate": (ctypes.c_int, [_vp, _i64, _vp, _i64, _i32, _i32, _i32, _vp, _vp, _vp]),
 }
 
 
@@ -535,3 +536,16 @@ def arrol_prune_bernoulli(s_norm, uniforms, p_lut, want_p=False, stream=None):
                                      out["survivor_idx"].data_ptr(), out["n_survivors"].data_ptr(), _stream(stream))
     _check("arrol_prune_bernoulli", rc)
     return out
+
+
+@_on_stream
+def arrol_probe_mfma_rate(a, b, shape=16, n_workgroups=256, iters=1000, out_sink=None, stream=None):
+    """Measurement aid: register-only bf16 MFMA loop on the values of a and b (bf16, whole 512-element
+    fragments).  Returns (sink fp32 [n_workgroups * 512], flop count of the launch)."""
+    sink = out_sink if out_sink is not None else torch.empty(n_workgroups * 512, dtype=torch.float32, device=a.device)
+    flop = ctypes.c_double(0.0)
+    rc = lib().arrol_probe_mfma_rate(_ptr(a, torch.bfloat16, "a"), a.numel(), _ptr(b, torch.bfloat16, "b"), b.numel(),
+                                     shape, n_workgroups, iters, _ptr(sink, torch.float32, "sink"),
+                                     ctypes.byref(flop), _stream(stream))
+    _check("arrol_probe_mfma_rate", rc)
+    return sink, flop.value

@@ -12,7 +12,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_DIR = os.path.join(HERE, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libarrol.so")
-SOURCES = ["score.hip", "score_mlp.hip", "train.hip", "select.hip", "compact.hip", "logprob.hip", "vote.hip", "confidence.hip", "grpo.hip", "policy.hip", "api.hip"]
+SOURCES = ["score.hip", "score_mlp.hip", "train.hip", "select.hip", "compact.hip", "logprob.hip", "vote.hip", "confidence.hip", "grpo.hip", "policy.hip", "probe.hip", "api.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

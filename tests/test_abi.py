@@ -195,6 +195,14 @@ def test_bad_arguments_are_rejected_on_the_host(pkg):
     assert L.arrol_prune_bernoulli(fake, fake, -1, fake, 128, None, fake, fake, fake, None) == -1
     assert L.arrol_prune_bernoulli(fake, fake, 8, fake, 128, None, fake, fake, None, None) == -1
     assert L.arrol_prune_bernoulli(None, fake, 8, fake, 128, None, fake, fake, fake, None) == -1
+    # MFMA rate probe: unknown shape, partial fragments, misaligned operands, workgroup count, null sink
+    assert L.arrol_probe_mfma_rate(fake, 512, fake, 512, 8, 4, 1, fake, None, None) == -1
+    assert L.arrol_probe_mfma_rate(fake, 500, fake, 512, 16, 4, 1, fake, None, None) == -1
+    assert L.arrol_probe_mfma_rate(fake, 512, fake, 0, 16, 4, 1, fake, None, None) == -1
+    assert L.arrol_probe_mfma_rate(ctypes.c_void_p(0x1008), 512, fake, 512, 16, 4, 1, fake, None, None) == -1
+    assert L.arrol_probe_mfma_rate(fake, 512, fake, 512, 16, 0, 1, fake, None, None) == -1
+    assert L.arrol_probe_mfma_rate(fake, 512, fake, 512, 32, 4, -1, fake, None, None) == -1
+    assert L.arrol_probe_mfma_rate(fake, 512, fake, 512, 32, 4, 1, None, None, None) == -1
 
 
 def test_binding_refuses_cpu_tensors(pkg):
