@@ -52,7 +52,7 @@ extern "C" {
 #define ARROL_MAX_GROUP 64      /* largest G (arrol_select) and C (arrol_weighted_vote) */
 #define ARROL_FIXED_POINT_BITS 30
 
-/* Library version (major*10000 + minor*100 + patch). */
+/* Library version (major*10000 + minor*100 + patch); changes whenever an argument list of this header does. */
 int arrol_version(void);
 /* Static, NUL-terminated description of a return code. */
 const char* arrol_error_string(int code);

@@ -38,6 +38,7 @@ class Policy(ctypes.Structure):
 
 
 _lib = None
+ABI_VERSION = 200     # arrol_version() of the library whose argument lists _SIGNATURES describes
 
 _vp, _i32, _i64, _f32, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
 _SIGNATURES = {
@@ -87,6 +88,12 @@ def lib():
             raise RuntimeError("libarrol.so is not built (%s missing): run "
                                "`python -m paper_2603_24840_amd.build`; there is no fallback path" % LIB_PATH)
         handle = ctypes.CDLL(LIB_PATH)
+        missing = [name for name in _SIGNATURES if not hasattr(handle, name)]
+        handle.arrol_version.restype, handle.arrol_version.argtypes = _SIGNATURES["arrol_version"]
+        if missing or handle.arrol_version() != ABI_VERSION:
+            raise RuntimeError("%s is a stale build (version %d, this binding is written for %d%s): rebuild with "
+                               "`python -m paper_2603_24840_amd.build`" % (LIB_PATH, handle.arrol_version(), ABI_VERSION,
+                                                                          "; missing " + ", ".join(missing) if missing else ""))
         for name, (res, args) in _SIGNATURES.items():
             fn = getattr(handle, name)
             fn.restype, fn.argtypes = res, args

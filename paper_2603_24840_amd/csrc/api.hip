@@ -1,7 +1,7 @@
 // Version and error strings of the ARRoL C ABI.
 #include "common.h"
 
-extern "C" int arrol_version(void) { return 100; }
+extern "C" int arrol_version(void) { return 200; }
 
 extern "C" const char* arrol_error_string(int code) {
     switch (code) {
