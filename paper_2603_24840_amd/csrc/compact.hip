@@ -7,7 +7,8 @@
 //         destination block tables / lengths / source map / page count.
 //   copy  HBM streaming: one 512-lane workgroup per (layer, K|V, survivor, logical page) chunk,
 //         every lane moving 16 bytes per access (non-temporal), the loads of a 16 KiB pass issued
-//         before its stores; extra workgroups move the token rows.
+//         before its stores; extra workgroups move the token rows.  Within a (layer, K|V) slab the
+//         grid visits the destination pages as 8 interleaved ascending streams (stream_order).
 #include "common.h"
 
 namespace {
@@ -15,6 +16,36 @@ namespace {
 constexpr int kPlanThreads = 1024;
 constexpr int kCopyThreads = 512;  // measured: 512 lanes x 2 accesses per 16 KiB chunk streams fastest
 constexpr int kCopyUnroll = 2;     // 16-byte accesses per lane issued before the stores
+constexpr unsigned kCopyStreams = 8;
+
+// Visiting order of n equally sized pieces of work whose addresses ascend with their index: position k of the
+// launch order takes piece stream_order(k, n).  The n pieces are cut into kCopyStreams contiguous parts (the first
+// ones one piece longer when n is no multiple); consecutive positions take the next piece of
+// consecutive parts, so the workgroups in flight at any time write to (and, for sorted sources, read from) 8
+// regions spread over the slab instead of one.  A bijection of [0, n) for every n >= 1.  Measured on the
+// benchmark pools against plain ascending order: +4 % for the out-of-place copy with 32 KiB chunks (6.0-6.1 TB/s
+// on the 120 and 155 GB pools), +1 % with 16 KiB chunks, +10 % for the in-place copy with 16 KiB chunks; 2, 4,
+// 16 and 32 streams were all slower than 8 on the large pools.
+__device__ __forceinline__ unsigned stream_order(unsigned k, unsigned n) {
+    const unsigned len = (n + kCopyStreams - 1) / kCopyStreams;     // pieces of a long part
+    const unsigned n_long = n - (len - 1) * kCopyStreams;           // parts 0 .. n_long-1 hold len pieces, the rest len-1
+    // round `round` takes piece `round` of every part that has one: in the last round (len - 1) only the n_long
+    // long parts, and k < n leaves exactly those
+    const unsigned round = k / kCopyStreams, part = k - round * kCopyStreams;
+    return (part < n_long ? part * len : n_long * len + (part - n_long) * (len - 1)) + round;
+}
+
+// compute units of the current device, looked up once per device (0 on failure)
+int compute_units() {
+    static std::atomic<int> cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+    int n = cached[dev].load(std::memory_order_acquire);
+    if (n > 0) return n;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 0;
+    cached[dev].store(n, std::memory_order_release);
+    return n;
+}
 
 __device__ __forceinline__ int pages_of(const int32_t* seq_len_src, int src, int n_src, int page_tokens, int ppr) {
     if (src < 0 || src >= n_src) return 0;
@@ -83,10 +114,10 @@ __global__ __launch_bounds__(kCopyThreads) void compact_copy_kernel(
     const int32_t* __restrict__ tokens_src, int32_t* __restrict__ tokens_dst, int max_len) {
     const int64_t bid = blockIdx.x;
     if (bid < kv_blocks) {
-        // bid = slab * (n_keep * ppr) + r * ppr + p : consecutive workgroups write consecutive pages
+        // bid = slab * (n_keep * ppr) + position; the position's slot r * ppr + p follows stream_order
         const int64_t slots = static_cast<int64_t>(n_keep) * ppr;
         const int64_t slab = bid / slots;
-        const int64_t slot = bid - slab * slots;
+        const int64_t slot = stream_order(static_cast<unsigned>(bid - slab * slots), static_cast<unsigned>(slots));
         const int r = static_cast<int>(slot / ppr), p = static_cast<int>(slot - static_cast<int64_t>(r) * ppr);
         const int b0 = base[r];
         if (p >= base[r + 1] - b0) return;
@@ -362,30 +393,21 @@ __global__ __launch_bounds__(kPlanThreads) void inplace_fused_plan_kernel(
     }
 }
 
-// pair k of the mover -> hole list, every (layer, K|V) slab: one workgroup per (slab, k), k below the
-// host-side bound on the pair count; pairs beyond the device-side count exit at once.  Both lists ascend.
-// The order in which the grid visits (slab, k) is chosen on the host from measurements of the pool sizes of
-// the benchmark configurations: slab by slab (group == 0) is fastest for 16 KiB chunks (5.16 TB/s on the
-// 8.6 GB pool against 4.7 for the grouped order), `group` = 16 consecutive pairs per slab visit, all slabs
-// before the next 16 pairs, for 32 KiB chunks (5.88 TB/s on the 155 GB pool and 5.65 on the 120 GB one
-// against 5.39 slab by slab).  Numbering only the m * n_slabs real copies (no idle workgroups in between),
-// neighbours on different slabs and a scrambled pair order all measured slower than both.
+// Copy of the mover -> hole pairs (both lists ascend), every (layer, K|V) slab.  The host knows only a bound on the
+// pair count (the exact one is in counters[1] on the device), and which form is fastest depends on the chunk size;
+// both forms were measured on the pools of the benchmark configurations.
+//
+// Chunks below 32 KiB: one workgroup per (slab, position), slab by slab, position < the host-side bound; positions
+// beyond the device-side count exit at once, the others take pair stream_order(position, count) - 5.8-5.9 TB/s on
+// the 8.6 GB pool of 16 KiB chunks against 5.1-5.4 in ascending pair order (a persistent grid: 5.0-5.3).
 __global__ __launch_bounds__(kCopyThreads) void inplace_copy_pairs_kernel(
     u32x4* __restrict__ kv, int64_t chunk_vec, int64_t P, const int32_t* __restrict__ hole_list,
-    const int32_t* __restrict__ mover_list, const int32_t* __restrict__ counters, unsigned m_bound, unsigned group) {
-    const unsigned bid = blockIdx.x;
-    unsigned slab, k;
-    if (group == 0) {
-        slab = bid / m_bound;
-        k = bid - slab * m_bound;
-    } else {
-        const unsigned n_slabs = gridDim.x / m_bound;
-        const unsigned per_group = n_slabs * group;
-        const unsigned grp = bid / per_group, rem = bid - grp * per_group;
-        slab = rem / group;
-        k = grp * group + (rem - slab * group);     // the host rounds m_bound up to whole groups
-    }
-    if (static_cast<int>(k) >= counters[1]) return;
+    const int32_t* __restrict__ mover_list, const int32_t* __restrict__ counters, unsigned m_bound) {
+    const unsigned slab = blockIdx.x / m_bound;
+    const unsigned pos = blockIdx.x - slab * m_bound;
+    const unsigned n_pairs = static_cast<unsigned>(counters[1]);
+    if (pos >= n_pairs) return;
+    const unsigned k = stream_order(pos, n_pairs);
     const u32x4* s = kv + (static_cast<int64_t>(slab) * P + mover_list[k]) * chunk_vec;
     u32x4* d = kv + (static_cast<int64_t>(slab) * P + hole_list[k]) * chunk_vec;
     for (int64_t v0 = 0; v0 < chunk_vec; v0 += kCopyThreads * kCopyUnroll) {
@@ -400,6 +422,41 @@ __global__ __launch_bounds__(kCopyThreads) void inplace_copy_pairs_kernel(
             const int64_t v = v0 + u * kCopyThreads + threadIdx.x;
             if (v < chunk_vec) __builtin_nontemporal_store(x[u], d + v);
         }
+    }
+}
+
+// Chunks of 32 KiB and more: a persistent grid (4 workgroups per compute unit) walks the count * n_slabs copies
+// with the slab as the fast index, workgroup b taking copies b, b + grid, b + 2 grid, ...: no workgroup is launched
+// only to exit (with one workgroup per copy, half of a bound-sized grid is idle on the benchmark pools and the
+// dispatch of those idle workgroups alone costs 7 %).  6.15-6.3 TB/s on the 120 and 155 GB pools against 5.8-5.9
+// for one workgroup per copy in its best order; walking pair-fast instead: 5.2.  The loop ends for every workgroup
+// after at most ceil(count * n_slabs / grid) copies.
+__global__ __launch_bounds__(kCopyThreads) void inplace_copy_walk_kernel(
+    u32x4* __restrict__ kv, int64_t chunk_vec, int64_t P, const int32_t* __restrict__ hole_list,
+    const int32_t* __restrict__ mover_list, const int32_t* __restrict__ counters, unsigned n_slabs) {
+    const unsigned n_pairs = static_cast<unsigned>(counters[1]);
+    // copy = k * n_slabs + slab, advanced by gridDim.x per step without a division in the loop
+    const unsigned step_k = gridDim.x / n_slabs, step_slab = gridDim.x - step_k * n_slabs;
+    unsigned k = blockIdx.x / n_slabs, slab = blockIdx.x - k * n_slabs;
+    while (k < n_pairs) {
+        const u32x4* s = kv + (static_cast<int64_t>(slab) * P + mover_list[k]) * chunk_vec;
+        u32x4* d = kv + (static_cast<int64_t>(slab) * P + hole_list[k]) * chunk_vec;
+        for (int64_t v0 = 0; v0 < chunk_vec; v0 += kCopyThreads * kCopyUnroll) {
+            u32x4 x[kCopyUnroll];
+#pragma unroll
+            for (int u = 0; u < kCopyUnroll; ++u) {
+                const int64_t v = v0 + u * kCopyThreads + threadIdx.x;
+                if (v < chunk_vec) x[u] = __builtin_nontemporal_load(s + v);
+            }
+#pragma unroll
+            for (int u = 0; u < kCopyUnroll; ++u) {
+                const int64_t v = v0 + u * kCopyThreads + threadIdx.x;
+                if (v < chunk_vec) __builtin_nontemporal_store(x[u], d + v);
+            }
+        }
+        k += step_k;
+        slab += step_slab;
+        if (slab >= n_slabs) { slab -= n_slabs; ++k; }
     }
 }
 
@@ -577,16 +634,22 @@ extern "C" int arrol_compact_inplace(void* kv, arrol_kv_layout layout, const int
                      hole_list, mover_list, counters, block_table_dst, seq_len_dst, src_of_dst, n_pages_used, n_moved);
         if (arrol_launch_failed()) return arrol_launch_status();
         // no more pairs than survivor pages, than dead pages (P - live >= holes), or than half the pool
-        int64_t m_bound = slots < P / 2 ? slots : P / 2;
+        const int64_t m_bound = slots < P / 2 ? slots : P / 2;
         const int n_slabs = layout.n_layers * 2;
-        const unsigned group = chunk_bytes >= 32768 ? 16u : 0u;   // see inplace_copy_pairs_kernel
-        if (group) m_bound = (m_bound + group - 1) / group * group;
-        const int64_t blocks = m_bound * n_slabs;
-        if (blocks > INT32_MAX) return ARROL_EINVAL;
-        if (blocks > 0)
+        if (m_bound == 0) return arrol_launch_status();
+        if (chunk_bytes >= 32768) {
+            const int n_cu = compute_units();
+            if (n_cu <= 0) return ARROL_EHIP;
+            arrol_launch(inplace_copy_walk_kernel, dim3(static_cast<unsigned>(n_cu) * 4u), dim3(kCopyThreads), 0, st,
+                         static_cast<u32x4*>(kv), chunk_bytes / 16, P, hole_list, mover_list, counters,
+                         static_cast<unsigned>(n_slabs));
+        } else {
+            const int64_t blocks = m_bound * n_slabs;
+            if (blocks > INT32_MAX) return ARROL_EINVAL;
             arrol_launch(inplace_copy_pairs_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kCopyThreads), 0, st,
                          static_cast<u32x4*>(kv), chunk_bytes / 16, P, hole_list, mover_list, counters,
-                         static_cast<unsigned>(m_bound), group);
+                         static_cast<unsigned>(m_bound));
+        }
         return arrol_launch_status();
     }
     if (P > 0) {

@@ -59,6 +59,23 @@ def test_inplace_ragged(A, W, head_dim, pt, n_prompts, G, K, extra):
     run_case(A, kv, bt, sl, pick)
 
 
+@pytest.mark.parametrize("n_prompts,G,K,extra,pt", [(5, 6, 3, 3, 16), (300, 8, 4, 77, 16), (1, 2, 1, 0, 16), (40, 4, 2, 9, 32)])
+def test_inplace_chunks_of_32_kib_and_more(A, W, n_prompts, G, K, extra, pt):
+    """head_dim 128 x 8 KV heads x 16 tokens = 32 KiB per chunk (64 KiB with 32-token pages): the copy runs as a
+    persistent grid there - fewer copies than workgroups, and several copies per workgroup."""
+    print("[case] inplace 32 KiB chunks prompts=%d G=%d K=%d page=%d" % (n_prompts, G, K, pt), flush=True)
+    cfg = W.shrink(W.CONFIGS["tiny"], n_prompts=n_prompts, G=G, K=K, head_dim=128, page_tokens=pt, ckpt_len=37 * pt // 16,
+                   n_layers=2, n_kv_heads=8)
+    assert cfg.chunk_bytes >= 32768
+    kv, bt, sl, _ = W.compact_inputs(cfg, DEV, extra_pages=extra, ragged=True)
+    g = torch.Generator(device="cpu"); g.manual_seed(n_prompts)
+    pick = torch.stack([torch.sort(torch.randperm(G, generator=g)[:K])[0] + i * G
+                        for i in range(n_prompts)]).reshape(-1).to(torch.int32).to(DEV)
+    _, ref = run_case(A, kv, bt, sl, pick)
+    if n_prompts == 300:
+        assert ref["n_moved"] * 4 > 1024      # more copies than the grid has workgroups
+
+
 def test_inplace_degenerate_cases(A, W):
     cfg = W.CONFIGS["tiny"]
     kv, bt, sl, _ = W.compact_inputs(cfg, DEV)
