@@ -167,6 +167,21 @@ def test_compact_ragged_and_odd_chunks(A, W, head_dim, pt, ragged, extra):
         assert ref["n_pages_used"] < cfg.n_keep * cfg.pages_per_rollout
 
 
+@pytest.mark.parametrize("head_dim,pt,n_prompts", [(128, 16, 7), (136, 16, 3), (128, 48, 2)])
+def test_compact_chunks_of_32_kib_and_more(A, W, head_dim, pt, n_prompts):
+    """8 KV heads: 32 KiB chunks (34 KiB with head_dim 136: a ragged last pass; 96 KiB with 48-token pages: three
+    passes) take the deeper-unrolled copy; page counts that are no multiple of the 8 streams of the visiting order."""
+    say("compact 32 KiB+ hd=%d page=%d prompts=%d" % (head_dim, pt, n_prompts))
+    cfg = W.shrink(W.CONFIGS["tiny"], n_prompts=n_prompts, G=5, K=3, head_dim=head_dim, page_tokens=pt, ckpt_len=37 * pt // 16,
+                   n_layers=2, n_kv_heads=8)
+    assert cfg.chunk_bytes >= 32768
+    kv, bt, sl, tok = W.compact_inputs(cfg, DEV, extra_pages=3, ragged=True)
+    g = torch.Generator(device="cpu"); g.manual_seed(n_prompts)
+    pick = torch.stack([torch.sort(torch.randperm(cfg.G, generator=g)[:cfg.K])[0] + i * cfg.G
+                        for i in range(cfg.n_prompts)]).reshape(-1).to(torch.int32).to(DEV)
+    run_compact_case(A, kv, bt, sl, tok, pick, cfg.n_keep * cfg.pages_per_rollout + 1)
+
+
 def test_compact_never_reads_pruned_pages_and_is_deterministic(A, W):
     cfg = W.shrink(W.CONFIGS["tiny"], n_prompts=8)
     kv, bt, sl, tok = W.compact_inputs(cfg, DEV, extra_pages=7)
