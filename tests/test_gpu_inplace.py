@@ -96,9 +96,14 @@ def test_inplace_degenerate_cases(A, W):
     assert row[1] == -1 and row[2] == -1 and 0 <= row[0] < 6 and 0 <= row[3] < 6
 
 
-def test_inplace_llama1b_full_size(A, W):
-    cfg = W.CONFIGS["llama1b"]
-    print("[case] inplace llama1b full pool; oracle on 2 of 16 layers, content property on all", flush=True)
+@pytest.mark.parametrize("name", ["llama1b", "qwen8b"])
+def test_inplace_full_size(A, W, name):
+    """llama1b: 8.6 GB pool of 16 KiB chunks (one workgroup per copy); qwen8b: 155 GB pool of 32 KiB chunks (the
+    persistent walk, offsets far beyond 4 GiB).  The oracle runs on the first and the last layer, every layer is
+    checked by a fingerprint of every survivor page."""
+    import gc
+    cfg = W.CONFIGS[name]
+    print("[case] inplace %s full pool; oracle on 2 of %d layers, content property on all" % (name, cfg.n_layers), flush=True)
     kv, bt, sl, _ = W.compact_inputs(cfg, DEV)
     _, surv_o = oracle_survivors(O, npy(W.select_inputs(cfg, DEV)), cfg)      # survivors from the oracle's selection
     surv = to_dev(surv_o, DEV)
@@ -116,6 +121,9 @@ def test_inplace_llama1b_full_size(A, W):
     flat_new = out["block_table_dst"].reshape(-1).long()
     assert int(flat_new.max()) == n_live - 1 and torch.unique(flat_new).numel() == n_live
     assert torch.equal(kv[:, :, flat_new, 0, 0, :4].view(torch.int16), probe.view(torch.int16))
+    del kv, probe, host_before, ref
+    gc.collect()
+    torch.cuda.empty_cache()
 
 
 def test_inplace_pool_beyond_the_one_launch_planner(A, W):
